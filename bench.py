@@ -1,0 +1,144 @@
+#!/usr/bin/env python3
+"""Headline benchmark: fused fp16 GEMM C = ReLU(A.B + bias), M = N = K = 4096, on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f16|bf16] [--k 4096|1024] [--no-cpu-baseline]
+
+One step = one pass of the whole hot path over one batch of synthetic input: block-level task mapping,
+cooperative predicated loads, double-buffered LDS staging, MFMA contraction, fused bias+ReLU epilogue and
+store -- a single hidet_gemm call.  Inputs are resident in HBM before the timed region.  Tuning (one
+enumeration of the schedule space) happens before the warm-up and is reported separately.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}  # 256 CUs x 4 SIMDs x FLOP/clk x 2.4 GHz (dense MFMA)
+
+# HBM bytes per launch of the dominant kernel at 4096^3, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+# (profiles/gemm_f16_4096_pmc.txt); None until measured for the workload at hand.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"])
+    ap.add_argument("--k", type=int, default=4096)
+    ap.add_argument("--config", type=int, default=None, help="force a tile configuration instead of tuning")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by output tiles without any exchange; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2210_09603_amd import binding as hb
+    from paper_2210_09603_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    hb.lib()  # raises if the HIP extension has not been built
+
+    dt = args.dtype
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[dt]
+    c = wl.config5(dt, K=args.k)
+    M, N, K = c["M"], c["N"], c["K"]
+
+    def dev(stored):
+        import numpy as np
+        if dt == "bf16":
+            return torch.from_numpy(np.ascontiguousarray(stored).view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+
+    A, B, bias = dev(c["A"]), dev(c["B"]), dev(c["bias"])
+    C = torch.empty((M, N), dtype=tdt, device="cuda")
+    epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True)
+
+    t0 = time.perf_counter()
+    if args.config is None:
+        best_cfg, best_us = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=10)
+    else:
+        best_cfg, best_us = args.config, float("nan")
+    tune_s = time.perf_counter() - t0
+    cfg_info = hb.hidet_config_info(best_cfg)
+
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        hb.hidet_gemm(A, B, C, epilogue=epi, stream=stream, config=best_cfg)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(args.steps):
+        hb.hidet_gemm(A, B, C, epilogue=epi, stream=stream, config=best_cfg)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * M * N * K
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+
+    algo_bytes = (M * K + K * N + M * N + N) * 2  # every operand and the output once
+    out = {
+        "metric": "fused GEMM/implicit-GEMM conv TFLOP/s and % of MI355X peak MFMA, 1 GPU",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": dt,
+        "data": "synthetic",
+        "config": {
+            "workload": "cfg5: fused %s GEMM C=ReLU(A.B+bias), M=N=%d, K=%d, row-major, U(-1,1), seed %d" % (dt, M, K, c["seed"]),
+            "tile_config": best_cfg,
+            "tile": "%dx%dx%d, %dx%d waves, mfma %d" % (cfg_info["block_m"], cfg_info["block_n"], cfg_info["block_k"],
+                                                         cfg_info["waves_m"], cfg_info["waves_n"], cfg_info["mfma"]),
+            "tuning_seconds": round(tune_s, 3),
+            "pct_of_peak_mfma": round(100.0 * tflops / PEAK_TFLOPS[dt], 2),
+            "algorithmic_hbm_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        },
+        "roofline": {
+            "bound": "mfma",
+            "achieved": round(tflops, 2),
+            "peak": PEAK_TFLOPS[dt],
+            "unit": "TFLOP/s",
+            "frac": round(tflops / PEAK_TFLOPS[dt], 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((dt, M, N, K)),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        A64, B64, b64 = wl.widen(c["A"], dt), wl.widen(c["B"], dt), wl.widen(c["bias"], dt)
+        rows, t = 32, 0.0
+        while True:  # grow the row sample until the oracle has worked for about 10 s
+            t0 = time.perf_counter()
+            oracle.gemm(A64, B64, bias=b64, relu=True, rows=(0, rows))
+            t = time.perf_counter() - t0
+            if t >= 8.0 or rows >= M:
+                break
+            rows = min(M, max(rows * 2, int(rows * 10.0 / max(t, 1e-3))))
+        out["cpu_baseline"] = {
+            "value": round(2.0 * rows * N * K / t / 1e12, 6),
+            "unit": "TFLOP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "first %d of %d rows of C (all %d columns, full K=%d), fp64, %.1f s" % (rows, M, N, K, t),
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,184 @@
+/*
+ * hidet_mi355x.h -- C ABI of the MI355X (gfx950) fused matrix-multiplication library.
+ *
+ * The library implements the scheduled matrix-multiplication tensor program of the Hidet paper
+ * (tiled over M and N into independent workgroup tasks, K tiled inside each workgroup, cooperative
+ * loads to on-chip memory, double buffering, matrix-core contraction; Sections 2.2 and 3.1), reused
+ * for convolution through the img2col formulation (Sections 5.2 and 6.3.4) and extended by
+ * post-scheduling fusion of elementwise prologue/epilogue operators (Sections 4.2 and 5.2).
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates no device
+ *     memory, launches asynchronously on the HIP stream passed as `stream` (a hipStream_t cast to
+ *     void*, NULL = the default stream) and never synchronises, except hidet_tune_* which time
+ *     kernels and therefore synchronise the stream.
+ *   - Matrices are row-major with explicit leading dimensions counted in elements.
+ *   - Products of fp16/bf16 inputs are accumulated in fp32; fp32 inputs are multiplied and
+ *     accumulated in fp32.  The output is rounded once (nearest-even) to `out` after the epilogue.
+ *   - Sizes are arbitrary: tiles that stick out of the problem are handled by predicated loads and
+ *     stores (the hardware-centric schedule space of Section 4.3 does not depend on input sizes).
+ *   - On any status other than HIDET_OK nothing has been launched and no output byte was written.
+ *     M == 0, N == 0 or batch == 0 is an OK no-op; K == 0 writes C = epilogue(0).
+ *   - Thread safety: entry points may be called from several host threads; the tuned-config cache
+ *     is guarded by a mutex.
+ */
+#ifndef HIDET_MI355X_H_
+#define HIDET_MI355X_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HIDET_OK = 0,
+  HIDET_ERR_INVALID_ARG = 1, /* null pointer, negative size, leading dimension too small, bad enum */
+  HIDET_ERR_UNSUPPORTED = 2, /* dtype combination, dilation/groups, index range beyond 2^31 elements */
+  HIDET_ERR_ALIGNMENT = 3,   /* pointer not aligned to its element size */
+  HIDET_ERR_NO_CONFIG = 4,   /* config index out of range, or config not applicable to this problem */
+  HIDET_ERR_LAUNCH = 5       /* the HIP runtime refused the launch */
+} hidet_status_t;
+
+typedef enum { HIDET_F32 = 0, HIDET_F16 = 1, HIDET_BF16 = 2 } hidet_dtype_t;
+typedef enum { HIDET_BIAS_NONE = 0, HIDET_BIAS_PER_COL = 1 /* length N */, HIDET_BIAS_PER_ROW = 2 /* length M */ } hidet_bias_axis_t;
+typedef enum { HIDET_ACT_NONE = 0, HIDET_ACT_RELU = 1 } hidet_act_t;
+
+/*
+ * Fused epilogue: the elementwise ("bijective") operators that post-scheduling fusion folds into
+ * the store of each output element (Section 4.2; Section 5.2 describes how an epilogue rewrites the
+ * value and the indices of every output store).  Applied in fp32, in this order:
+ *     v = alpha * acc;  v += bias[j] (per col) or bias[i] (per row);  v += residual[i][j];
+ *     v = max(v, 0) if act == HIDET_ACT_RELU;  out = round_to_out_dtype(v)
+ * bias and residual have the OUTPUT dtype.  residual has the shape of the output and its own
+ * leading dimension; in batched calls it advances by batch_stride_residual elements per batch
+ * entry, while bias is shared by all batch entries.  A NULL epilogue pointer means identity
+ * (alpha = 1, nothing else).  struct_size must be sizeof(hidet_epilogue_t).
+ */
+typedef struct {
+  uint32_t struct_size;
+  float alpha;
+  const void* bias;
+  int32_t bias_axis; /* hidet_bias_axis_t */
+  int32_t act;       /* hidet_act_t */
+  const void* residual;
+  int64_t ld_residual;
+  int64_t batch_stride_residual;
+} hidet_epilogue_t;
+
+/*
+ * C[M,N] = epilogue( op(A)[M,K] . op(B)[K,N] )            (matmul definition, Section 2.3)
+ * transA == 0: A is stored M x K (lda >= K); transA != 0: A is stored K x M (lda >= M).
+ * transB == 0: B is stored K x N (ldb >= N); transB != 0: B is stored N x K (ldb >= K).
+ * `in` is the dtype of A and B, `out` the dtype of C, bias and residual.  Supported pairs:
+ * (F32,F32), (F16,F16), (F16,F32), (BF16,BF16), (BF16,F32).
+ * The tile configuration is the cached tuning winner for this problem if hidet_tune_gemm has
+ * seen it, otherwise a size-based default.
+ */
+hidet_status_t hidet_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M, int64_t N, int64_t K,
+                          const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                          const hidet_epilogue_t* epi, void* stream);
+
+/*
+ * `batch` independent GEMMs; entry b uses A + b*strideA, B + b*strideB, C + b*strideC (strides in
+ * elements; a stride of 0 shares that operand across the batch, not allowed for C).
+ */
+hidet_status_t hidet_batched_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
+                                  int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                                  int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                                  const hidet_epilogue_t* epi, void* stream);
+
+/*
+ * y = epilogue( conv2d(x, w) ): NCHW input x[Nb][IC][H][W], OIHW weights w[OC][IC][KH][KW], NCHW
+ * output y[Nb][OC][OH][OW], OH = floor((H + 2*pad_h - KH)/stride_h) + 1 (same for OW), all three
+ * tensors dense.  Cross-correlation with zero padding, dilation 1, groups 1.  Computed as an
+ * implicit GEMM (Sections 5.2 and 6.3.4): GEMM M = OC, GEMM N = Nb*OH*OW, GEMM K = IC*KH*KW; the
+ * img2col gather is the fused prologue of the B operand and the NCHW index map is part of the
+ * fused epilogue, so no img2col matrix is ever materialised.  In the epilogue, bias (if any) must
+ * be HIDET_BIAS_PER_ROW, i.e. one value per output channel, and residual (if any) is a dense
+ * tensor of y's shape (ld_residual and batch_stride_residual are ignored).
+ */
+hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
+                                          int64_t OC, int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                          int64_t pad_h, int64_t pad_w, const void* x, const void* w, void* y,
+                                          const hidet_epilogue_t* epi, void* stream);
+
+/*
+ * Same three operations with an explicit tile configuration (index into the schedule space below);
+ * config < 0 behaves like the plain entry points.  HIDET_ERR_NO_CONFIG if the configuration cannot
+ * run this problem (wrong dtype class).
+ */
+hidet_status_t hidet_gemm_cfg(int32_t config, int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M,
+                              int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
+                              int64_t ldc, const hidet_epilogue_t* epi, void* stream);
+hidet_status_t hidet_batched_gemm_cfg(int32_t config, int32_t in, int32_t out, int32_t transA, int32_t transB,
+                                      int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                                      int64_t strideA, const void* B, int64_t ldb, int64_t strideB, void* C,
+                                      int64_t ldc, int64_t strideC, const hidet_epilogue_t* epi, void* stream);
+hidet_status_t hidet_conv2d_implicit_gemm_cfg(int32_t config, int32_t in, int32_t out, int64_t Nb, int64_t IC,
+                                              int64_t H, int64_t W, int64_t OC, int64_t KH, int64_t KW,
+                                              int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                              const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
+                                              void* stream);
+
+/*
+ * Hardware-centric schedule space (Section 4.3): a fixed list of tile configurations chosen from
+ * what the hardware offers (LDS capacity, registers, wavefronts per workgroup, matrix-core shapes),
+ * independent of problem sizes.  Index range: 0 .. hidet_config_count()-1.
+ */
+typedef struct {
+  int32_t block_m, block_n, block_k; /* workgroup tile */
+  int32_t waves_m, waves_n;          /* wavefront grid inside the workgroup: spatial(waves_m, waves_n) */
+  int32_t mfma;                      /* matrix-core tile edge: 32 (32x32xk) or 16 (16x16xk) */
+  int32_t is_f32;                    /* 1: configuration for fp32 inputs, 0: for fp16/bf16 inputs */
+  int32_t lds_bytes;                 /* LDS used by the two staging buffers */
+} hidet_config_info_t;
+int32_t hidet_config_count(void);
+hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info);
+
+/*
+ * Tuning (Section 5.1.3, template-based scheduling): run every applicable configuration of the
+ * schedule space on the caller's fused problem (same arguments as the batched GEMM / the conv),
+ * time `iters` launches of each with HIP events on `stream`, remember the fastest under a key made
+ * of (operation, dtypes, transposes, sizes, epilogue kind) and report it.  The output buffer is
+ * overwritten with valid results.  best_config / best_us may be NULL.  Synchronises `stream`.
+ */
+hidet_status_t hidet_tune_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
+                               int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                               int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                               const hidet_epilogue_t* epi, void* stream, int32_t iters, int32_t* best_config,
+                               float* best_us);
+hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W, int64_t OC,
+                                 int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                 int64_t pad_w, const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
+                                 void* stream, int32_t iters, int32_t* best_config, float* best_us);
+/* After a hidet_tune_* call: per-configuration mean microseconds of that run (negative = not applicable). */
+int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity);
+/* Forget every tuned entry. */
+void hidet_tune_clear(void);
+/* Persist / restore the tuned-config cache as a text file (host paths).  Returns HIDET_ERR_INVALID_ARG on I/O errors. */
+hidet_status_t hidet_tune_save(const char* path);
+hidet_status_t hidet_tune_load(const char* path);
+
+/*
+ * Task mappings (Section 5.1): the compile-time mappings the kernels are built from, plus the
+ * paper's worked examples, evaluated on the host so that tests can compare them with the
+ * definitions.  `expr` receives a string such as "repeat(4,1)*spatial(16,8)".  hidet_taskmap_tasks
+ * writes the worker's task list as (i, j) pairs into `tasks_ij` (2 * tasks int32 values).
+ */
+int32_t hidet_taskmap_count(void);
+hidet_status_t hidet_taskmap_info(int32_t index, char* expr, int32_t expr_capacity, int32_t* workers, int32_t* shape0,
+                                  int32_t* shape1, int32_t* tasks_per_worker);
+hidet_status_t hidet_taskmap_tasks(int32_t index, int32_t worker, int32_t* tasks_ij, int32_t capacity_pairs);
+/* Block-level mapping used at launch: tile (i, j) of workgroup `w` for a tiles_m x tiles_n grid with grouping `group`. */
+hidet_status_t hidet_block_task(int32_t tiles_m, int32_t tiles_n, int32_t group, int32_t w, int32_t* tile_i,
+                                int32_t* tile_j);
+
+const char* hidet_status_string(int32_t status);
+/* Library version string and the GPU architecture the kernels were compiled for ("gfx950"). */
+const char* hidet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIDET_MI355X_H_ */

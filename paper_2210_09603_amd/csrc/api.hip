@@ -1,0 +1,572 @@
+// C ABI of the library (see include/hidet_mi355x.h): argument validation, choice of the tile
+// configuration, the tuner that enumerates the hardware-centric schedule space, and the launch.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/hidet_mi355x.h"
+#include "registry.hpp"
+
+using namespace hidet;
+
+// ------------------------------------------------------------------------------------------------
+// Table of contents of the schedule space + the launchers registered by the instance objects.
+// ------------------------------------------------------------------------------------------------
+#define HIDET_ALL
+static const ConfigRow kConfigs[] = {
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA) {idx, BM, BN, BK, WM, WN, MI, TA, 0},
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA) {idx, BM, BN, BK, WM, WN, MI, TA, 1},
+#include "configs.def"
+#undef X16
+#undef X32
+};
+static const int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
+
+// weak: a development build may leave some (configuration, type) objects out; their table slots stay empty
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA)                                    \
+  extern "C" void hidet_register_##idx##_1(Registry*) __attribute__((weak));    \
+  extern "C" void hidet_register_##idx##_2(Registry*) __attribute__((weak));
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA) extern "C" void hidet_register_##idx##_0(Registry*) __attribute__((weak));
+#include "configs.def"
+#undef X16
+#undef X32
+
+static const Registry& registry() {
+  static Registry* r = [] {
+    Registry* reg = new Registry();
+    std::memset(reg, 0, sizeof(Registry));
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA)                  \
+  if (hidet_register_##idx##_1) hidet_register_##idx##_1(reg); \
+  if (hidet_register_##idx##_2) hidet_register_##idx##_2(reg);
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA) \
+  if (hidet_register_##idx##_0) hidet_register_##idx##_0(reg);
+#include "configs.def"
+#undef X16
+#undef X32
+    return reg;
+  }();
+  return *r;
+}
+#undef HIDET_ALL
+
+static_assert(sizeof(kConfigs) / sizeof(kConfigs[0]) <= kMaxConfigs, "raise kMaxConfigs");
+
+// ------------------------------------------------------------------------------------------------
+// Problem description shared by GEMM, batched GEMM and conv.
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+struct Problem {
+  int op = 0;  // 0 gemm (batched), 1 conv
+  int dtype = 0;
+  int transA = 0, transB = 0;
+  long long batch = 1;
+  int elem_mode = 0;  // 1: some operand is not 16-byte aligned -> element loads
+  GemmParams p{};
+  // conv-only key fields
+  long long Nb = 0, OC = 0;
+};
+
+int elem_size(int dtype) { return dtype == HIDET_F32 ? 4 : 2; }
+bool aligned(const void* ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; }
+constexpr long long kIntMax = 2147483647LL;
+
+hidet_status_t check_dtypes(int in, int out) {
+  if (in < 0 || in > 2 || out < 0 || out > 2) return HIDET_ERR_INVALID_ARG;
+  if (in != out) return HIDET_ERR_UNSUPPORTED;
+  return HIDET_OK;
+}
+
+hidet_status_t check_epilogue(const hidet_epilogue_t* epi, int dtype, bool conv) {
+  if (!epi) return HIDET_OK;
+  if (epi->struct_size != sizeof(hidet_epilogue_t)) return HIDET_ERR_INVALID_ARG;
+  if (epi->bias_axis < 0 || epi->bias_axis > 2 || epi->act < 0 || epi->act > 1) return HIDET_ERR_INVALID_ARG;
+  if (epi->bias_axis != HIDET_BIAS_NONE && !epi->bias) return HIDET_ERR_INVALID_ARG;
+  if (conv && epi->bias_axis == HIDET_BIAS_PER_COL) return HIDET_ERR_INVALID_ARG;
+  const size_t es = (size_t)elem_size(dtype);
+  if (epi->bias_axis != HIDET_BIAS_NONE && !aligned(epi->bias, es)) return HIDET_ERR_ALIGNMENT;
+  if (epi->residual && !aligned(epi->residual, es)) return HIDET_ERR_ALIGNMENT;
+  if (!(epi->alpha == epi->alpha)) return HIDET_ERR_INVALID_ARG;  // NaN scale
+  return HIDET_OK;
+}
+
+void fill_epilogue(GemmParams& p, const hidet_epilogue_t* epi) {
+  p.alpha = 1.0f;
+  p.bias = nullptr;
+  p.bias_axis = 0;
+  p.residual = nullptr;
+  p.ldr = 0;
+  p.strideR = 0;
+  p.relu = 0;
+  if (epi) {
+    p.alpha = epi->alpha;
+    p.bias_axis = epi->bias_axis;
+    p.bias = epi->bias_axis ? epi->bias : nullptr;
+    p.residual = epi->residual;
+    p.ldr = epi->ld_residual;
+    p.strideR = epi->batch_stride_residual;
+    p.relu = epi->act == HIDET_ACT_RELU;
+  }
+}
+
+hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int transB, long long batch, long long M,
+                                 long long N, long long K, const void* A, long long lda, long long strideA,
+                                 const void* B, long long ldb, long long strideB, void* C, long long ldc,
+                                 long long strideC, const hidet_epilogue_t* epi) {
+  hidet_status_t st = check_dtypes(in, out);
+  if (st != HIDET_OK) return st;
+  if (batch < 0 || M < 0 || N < 0 || K < 0) return HIDET_ERR_INVALID_ARG;
+  if (M > kIntMax || N > kIntMax || K > kIntMax || batch > kIntMax) return HIDET_ERR_UNSUPPORTED;
+  const bool empty = (batch == 0 || M == 0 || N == 0);
+  st = check_epilogue(epi, out, false);
+  if (st != HIDET_OK) return st;
+  if (!empty) {
+    if (!C) return HIDET_ERR_INVALID_ARG;
+    if (K > 0 && (!A || !B)) return HIDET_ERR_INVALID_ARG;
+    if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return HIDET_ERR_INVALID_ARG;
+    if (strideA < 0 || strideB < 0 || strideC < 0) return HIDET_ERR_INVALID_ARG;
+    if (batch > 1 && strideC < (M - 1) * ldc + N) return HIDET_ERR_INVALID_ARG;
+    if (epi && epi->residual) {
+      if (epi->ld_residual < N) return HIDET_ERR_INVALID_ARG;
+      if (epi->batch_stride_residual < 0) return HIDET_ERR_INVALID_ARG;
+    }
+    const size_t es = (size_t)elem_size(in);
+    if (!aligned(A, es) || !aligned(B, es) || !aligned(C, es)) return HIDET_ERR_ALIGNMENT;
+  }
+  pr.op = 0;
+  pr.dtype = in;
+  pr.transA = transA ? 1 : 0;
+  pr.transB = transB ? 1 : 0;
+  pr.batch = batch;
+  GemmParams& p = pr.p;
+  p.A = A;
+  p.B = B;
+  p.C = C;
+  p.M = (int)M;
+  p.N = (int)N;
+  p.K = (int)K;
+  p.lda = lda;
+  p.ldb = ldb;
+  p.ldc = ldc;
+  p.strideA = strideA;
+  p.strideB = strideB;
+  p.strideC = strideC;
+  fill_epilogue(p, epi);
+  const int vec = 16 / elem_size(in);
+  const bool a_vec = aligned(A, 16) && lda % vec == 0 && strideA % vec == 0;
+  const bool b_vec = aligned(B, 16) && ldb % vec == 0 && strideB % vec == 0;
+  pr.elem_mode = (a_vec && b_vec) ? 0 : 1;
+  const size_t va = 4 * (size_t)elem_size(out);
+  bool vs = aligned(C, va) && ldc % 4 == 0 && strideC % 4 == 0;
+  if (p.residual) vs = vs && aligned(p.residual, va) && p.ldr % 4 == 0 && p.strideR % 4 == 0;
+  p.vec_store = vs ? 1 : 0;
+  p.out_inner = 1;
+  p.out_outer = 0;
+  std::memset(&p.g, 0, sizeof(p.g));
+  return HIDET_OK;
+}
+
+hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, long long IC, long long H, long long W,
+                                 long long OC, long long KH, long long KW, long long sh, long long sw, long long ph,
+                                 long long pw, const void* x, const void* w, void* y, const hidet_epilogue_t* epi) {
+  hidet_status_t st = check_dtypes(in, out);
+  if (st != HIDET_OK) return st;
+  if (Nb < 0 || IC < 0 || H < 0 || W < 0 || OC < 0 || KH <= 0 || KW <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+    return HIDET_ERR_INVALID_ARG;
+  st = check_epilogue(epi, out, true);
+  if (st != HIDET_OK) return st;
+  const long long OH = (H + 2 * ph - KH) >= 0 ? (H + 2 * ph - KH) / sh + 1 : 0;
+  const long long OW = (W + 2 * pw - KW) >= 0 ? (W + 2 * pw - KW) / sw + 1 : 0;
+  const long long M = OC, N = Nb * OH * OW, K = IC * KH * KW;
+  if (M > kIntMax || N > kIntMax || K > kIntMax || Nb * IC * H * W > kIntMax || H + 2 * ph > 1000000 ||
+      W + 2 * pw > 1000000)
+    return HIDET_ERR_UNSUPPORTED;
+  const bool empty = (M == 0 || N == 0);
+  if (!empty) {
+    if (!y) return HIDET_ERR_INVALID_ARG;
+    if (K > 0 && (!x || !w)) return HIDET_ERR_INVALID_ARG;
+    const size_t es = (size_t)elem_size(in);
+    if (!aligned(x, es) || !aligned(w, es) || !aligned(y, es)) return HIDET_ERR_ALIGNMENT;
+  }
+  pr.op = 1;
+  pr.dtype = in;
+  pr.transA = 0;
+  pr.transB = 0;
+  pr.batch = 1;
+  pr.Nb = Nb;
+  pr.OC = OC;
+  GemmParams& p = pr.p;
+  p.A = w;
+  p.B = x;
+  p.C = y;
+  p.M = (int)M;
+  p.N = (int)N;
+  p.K = (int)K;
+  p.lda = K;
+  p.ldb = 0;
+  p.ldc = 0;
+  p.strideA = p.strideB = p.strideC = 0;
+  fill_epilogue(p, epi);
+  p.ldr = 0;
+  p.strideR = 0;
+  p.g = ConvGeom{(int)IC, (int)H, (int)W, (int)KH, (int)KW, (int)sh, (int)sw, (int)ph, (int)pw, (int)OH, (int)OW};
+  p.out_inner = OH * OW;
+  p.out_outer = OC * OH * OW;
+  const int vec = 16 / elem_size(in);
+  pr.elem_mode = (aligned(w, 16) && K % vec == 0) ? 0 : 1;
+  const size_t va = 4 * (size_t)elem_size(out);
+  bool vs = aligned(y, va) && p.out_inner % 4 == 0;
+  if (p.residual) vs = vs && aligned(p.residual, va);
+  p.vec_store = vs ? 1 : 0;
+  return HIDET_OK;
+}
+
+LaunchFn find_launcher(const Problem& pr, int config) {
+  if (config < 0 || config >= kNumConfigs) return nullptr;
+  const int variant = pr.op == 1 ? conv_variant(pr.elem_mode) : gemm_variant(pr.transA, pr.transB, pr.elem_mode);
+  return registry().fn[config][pr.dtype][variant];
+}
+
+// Size-based default when the problem has not been tuned: the largest tile that still yields at
+// least one workgroup per compute unit, else the configuration with the most workgroups.
+int default_config(const Problem& pr) {
+  const long long M = pr.p.M, N = pr.p.N;
+  int best = -1;
+  long long best_area = -1;
+  int most = -1;
+  long long most_blocks = -1;
+  for (int c = 0; c < kNumConfigs; ++c) {
+    if (!find_launcher(pr, c)) continue;
+    const ConfigRow& r = kConfigs[c];
+    const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch;
+    const long long area = (long long)r.bm * r.bn;
+    if (blocks >= 256 && area > best_area) {
+      best_area = area;
+      best = c;
+    }
+    if (blocks > most_blocks || (blocks == most_blocks && most >= 0 && area > (long long)kConfigs[most].bm * kConfigs[most].bn)) {
+      most_blocks = blocks;
+      most = c;
+    }
+  }
+  return best >= 0 ? best : most;
+}
+
+// ---- tuned-config cache ---------------------------------------------------------------------------
+std::mutex g_mutex;
+std::map<std::string, int> g_cache;
+std::vector<float> g_last_times;
+
+std::string problem_key(const Problem& pr) {
+  char buf[256];
+  const GemmParams& p = pr.p;
+  const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0);
+  if (pr.op == 0)
+    std::snprintf(buf, sizeof(buf), "gemm:t%d:%d%d:b%lld:%dx%dx%d:e%d:m%d", pr.dtype, pr.transA, pr.transB, pr.batch, p.M,
+                  p.N, p.K, epi_kind, pr.elem_mode);
+  else
+    std::snprintf(buf, sizeof(buf), "conv:t%d:n%lld:c%d:%dx%d:o%lld:k%dx%d:s%dx%d:p%dx%d:e%d:m%d", pr.dtype, pr.Nb, p.g.IC,
+                  p.g.H, p.g.W, pr.OC, p.g.KH, p.g.KW, p.g.sh, p.g.sw, p.g.ph, p.g.pw, epi_kind, pr.elem_mode);
+  return std::string(buf);
+}
+
+hidet_status_t launch(const Problem& pr_in, int config, hipStream_t stream) {
+  Problem pr = pr_in;
+  GemmParams& p = pr.p;
+  if (pr.batch == 0 || p.M == 0 || p.N == 0) return HIDET_OK;
+  if (config < 0) {
+    {
+      std::lock_guard<std::mutex> lock(g_mutex);
+      auto it = g_cache.find(problem_key(pr));
+      if (it != g_cache.end()) config = it->second;
+    }
+    if (config < 0 || !find_launcher(pr, config)) config = default_config(pr);
+  }
+  LaunchFn fn = find_launcher(pr, config);
+  if (!fn) return HIDET_ERR_NO_CONFIG;
+  const ConfigRow& r = kConfigs[config];
+  p.tiles_m = (p.M + r.bm - 1) / r.bm;
+  p.tiles_n = (p.N + r.bn - 1) / r.bn;
+  const long long total = (long long)p.tiles_m * p.tiles_n * pr.batch;
+  if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
+  p.total_blocks = (int)total;
+  // grouped traversal: each run of 32 consecutive workgroups (one die's share of a 256-tile wave)
+  // should cover a near-square patch of tiles
+  p.group = p.tiles_m >= 4 ? 4 : p.tiles_m;
+  if (fn(p, stream) != hipSuccess) return HIDET_ERR_LAUNCH;
+  return HIDET_OK;
+}
+
+hidet_status_t tune(const Problem& pr, hipStream_t stream, int iters, int32_t* best_config, float* best_us) {
+  if (iters <= 0) iters = 10;
+  std::vector<float> times(kNumConfigs, -1.0f);
+  int best = -1;
+  float best_t = 0.0f;
+  if (!(pr.batch == 0 || pr.p.M == 0 || pr.p.N == 0)) {
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return HIDET_ERR_LAUNCH;
+    for (int c = 0; c < kNumConfigs; ++c) {
+      if (!find_launcher(pr, c)) continue;
+      hidet_status_t st = launch(pr, c, stream);  // warm-up, also loads the code object
+      if (st != HIDET_OK) continue;
+      (void)hipEventRecord(e0, stream);
+      for (int i = 0; i < iters; ++i) launch(pr, c, stream);
+      (void)hipEventRecord(e1, stream);
+      if (hipEventSynchronize(e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+        return HIDET_ERR_LAUNCH;
+      }
+      float ms = 0.0f;
+      (void)hipEventElapsedTime(&ms, e0, e1);
+      times[c] = ms * 1000.0f / (float)iters;
+      if (best < 0 || times[c] < best_t) {
+        best = c;
+        best_t = times[c];
+      }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (best < 0) return HIDET_ERR_NO_CONFIG;
+    // leave the winner's output in the buffer
+    launch(pr, best, stream);
+    (void)hipStreamSynchronize(stream);
+  }
+  {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (best >= 0) g_cache[problem_key(pr)] = best;
+    g_last_times = times;
+  }
+  if (best_config) *best_config = best;
+  if (best_us) *best_us = best_t;
+  return HIDET_OK;
+}
+
+// ---- task-mapping instances exposed to tests ----------------------------------------------------------
+struct TaskMapEntry {
+  const char* expr;
+  int workers, shape0, shape1, tasks;
+  tmap::Task (*task)(int, int);
+};
+template <class M>
+TaskMapEntry tm_entry(const char* expr) {
+  return TaskMapEntry{expr, M::workers, M::shape0, M::shape1, M::tasks, [](int w, int q) { return M::task(w, q); }};
+}
+using namespace hidet::tmap;
+const TaskMapEntry kTaskMaps[] = {
+    // the paper's worked examples
+    tm_entry<Compose<Repeat<4, 1>, Spatial<16, 8>>>("repeat(4,1)*spatial(16,8)"),
+    tm_entry<Chain<Spatial<4, 2>, Repeat<2, 2>, Spatial<4, 8>, Repeat<4, 4>>>(
+        "spatial(4,2)*repeat(2,2)*spatial(4,8)*repeat(4,4)"),
+    tm_entry<Compose<Spatial<2, 2>, Repeat<2, 2>>>("spatial(2,2)*repeat(2,2)"),
+    tm_entry<Repeat<2, 2>>("repeat(2,2)"),
+    tm_entry<Spatial<2, 2>>("spatial(2,2)"),
+    tm_entry<Compose<Spatial<1, 3>, Spatial<2, 1>>>("spatial(1,3)*spatial(2,1)"),
+    tm_entry<Compose<Compose<Repeat<2, 1>, Spatial<2, 3>>, Repeat<1, 2>>>("repeat(2,1)*spatial(2,3)*repeat(1,2)"),
+    tm_entry<Compose<Repeat<2, 1>, Compose<Spatial<2, 3>, Repeat<1, 2>>>>("repeat(2,1)*spatial(2,3)*repeat(1,2)"),
+    // the mappings the headline kernel (256x256x64, 8 waves) is built from
+    tm_entry<LoadMapRowMajor<256, 8, 512>::Map>("repeat(4,1)*spatial(64,8)"),    // A tile, 256 rows x 8 chunks
+    tm_entry<LoadMapRowMajor<64, 32, 512>::Map>("repeat(4,1)*spatial(16,32)"),   // B tile, 64 k-rows x 32 chunks
+    tm_entry<Compose<Spatial<2, 4>, Repeat<4, 2>>>("spatial(2,4)*repeat(4,2)"),  // waves -> MFMA tiles
+    // fp32 A tile of the 128x128x16 configuration: threads walk down the rows first
+    tm_entry<LoadMapColMajor<128, 4, 256>::Map>("repeat(2,1)*spatial(2,128)"),
+    tm_entry<LoadMapColMajor<256, 4, 128>::Map>("repeat(4,2)*spatial(1,128)"),
+};
+const int kNumTaskMaps = (int)(sizeof(kTaskMaps) / sizeof(kTaskMaps[0]));
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// exported functions
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+hidet_status_t hidet_batched_gemm_cfg(int32_t config, int32_t in, int32_t out, int32_t transA, int32_t transB,
+                                      int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                                      int64_t strideA, const void* B, int64_t ldb, int64_t strideB, void* C,
+                                      int64_t ldc, int64_t strideC, const hidet_epilogue_t* epi, void* stream) {
+  Problem pr;
+  hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
+                                        C, ldc, strideC, epi);
+  if (st != HIDET_OK) return st;
+  if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  return launch(pr, config, (hipStream_t)stream);
+}
+
+hidet_status_t hidet_gemm_cfg(int32_t config, int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M,
+                              int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
+                              int64_t ldc, const hidet_epilogue_t* epi, void* stream) {
+  return hidet_batched_gemm_cfg(config, in, out, transA, transB, 1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, epi,
+                                stream);
+}
+
+hidet_status_t hidet_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M, int64_t N, int64_t K,
+                          const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                          const hidet_epilogue_t* epi, void* stream) {
+  return hidet_gemm_cfg(-1, in, out, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, epi, stream);
+}
+
+hidet_status_t hidet_batched_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
+                                  int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                                  int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                                  const hidet_epilogue_t* epi, void* stream) {
+  return hidet_batched_gemm_cfg(-1, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc,
+                                strideC, epi, stream);
+}
+
+hidet_status_t hidet_conv2d_implicit_gemm_cfg(int32_t config, int32_t in, int32_t out, int64_t Nb, int64_t IC,
+                                              int64_t H, int64_t W, int64_t OC, int64_t KH, int64_t KW,
+                                              int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                              const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
+                                              void* stream) {
+  Problem pr;
+  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
+                                        y, epi);
+  if (st != HIDET_OK) return st;
+  if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  return launch(pr, config, (hipStream_t)stream);
+}
+
+hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
+                                          int64_t OC, int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                          int64_t pad_h, int64_t pad_w, const void* x, const void* w, void* y,
+                                          const hidet_epilogue_t* epi, void* stream) {
+  return hidet_conv2d_implicit_gemm_cfg(-1, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
+                                        y, epi, stream);
+}
+
+int32_t hidet_config_count(void) { return kNumConfigs; }
+
+hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info) {
+  if (!info) return HIDET_ERR_INVALID_ARG;
+  if (config < 0 || config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  const ConfigRow& r = kConfigs[config];
+  info->block_m = r.bm;
+  info->block_n = r.bn;
+  info->block_k = r.bk;
+  info->waves_m = r.waves_m;
+  info->waves_n = r.waves_n;
+  info->mfma = r.mfma;
+  info->is_f32 = r.is_f32;
+  info->lds_bytes = 2 * (r.bm + r.bn) * r.bk * (r.is_f32 ? 4 : 2);
+  return HIDET_OK;
+}
+
+hidet_status_t hidet_tune_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
+                               int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                               int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                               const hidet_epilogue_t* epi, void* stream, int32_t iters, int32_t* best_config,
+                               float* best_us) {
+  Problem pr;
+  hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
+                                        C, ldc, strideC, epi);
+  if (st != HIDET_OK) return st;
+  return tune(pr, (hipStream_t)stream, iters, best_config, best_us);
+}
+
+hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W, int64_t OC,
+                                 int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                 int64_t pad_w, const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
+                                 void* stream, int32_t iters, int32_t* best_config, float* best_us) {
+  Problem pr;
+  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
+                                        y, epi);
+  if (st != HIDET_OK) return st;
+  return tune(pr, (hipStream_t)stream, iters, best_config, best_us);
+}
+
+int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  const int n = (int)g_last_times.size();
+  for (int i = 0; i < n && i < capacity; ++i) us_per_config[i] = g_last_times[i];
+  return n;
+}
+
+void hidet_tune_clear(void) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  g_cache.clear();
+}
+
+hidet_status_t hidet_tune_save(const char* path) {
+  if (!path) return HIDET_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  FILE* f = std::fopen(path, "w");
+  if (!f) return HIDET_ERR_INVALID_ARG;
+  for (const auto& kv : g_cache) std::fprintf(f, "%s %d\n", kv.first.c_str(), kv.second);
+  std::fclose(f);
+  return HIDET_OK;
+}
+
+hidet_status_t hidet_tune_load(const char* path) {
+  if (!path) return HIDET_ERR_INVALID_ARG;
+  FILE* f = std::fopen(path, "r");
+  if (!f) return HIDET_ERR_INVALID_ARG;
+  char key[256];
+  int cfg = 0;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  while (std::fscanf(f, "%255s %d", key, &cfg) == 2)
+    if (cfg >= 0 && cfg < kNumConfigs) g_cache[std::string(key)] = cfg;
+  std::fclose(f);
+  return HIDET_OK;
+}
+
+int32_t hidet_taskmap_count(void) { return kNumTaskMaps; }
+
+hidet_status_t hidet_taskmap_info(int32_t index, char* expr, int32_t expr_capacity, int32_t* workers, int32_t* shape0,
+                                  int32_t* shape1, int32_t* tasks_per_worker) {
+  if (index < 0 || index >= kNumTaskMaps) return HIDET_ERR_INVALID_ARG;
+  const TaskMapEntry& e = kTaskMaps[index];
+  if (expr && expr_capacity > 0) {
+    std::strncpy(expr, e.expr, (size_t)expr_capacity - 1);
+    expr[expr_capacity - 1] = 0;
+  }
+  if (workers) *workers = e.workers;
+  if (shape0) *shape0 = e.shape0;
+  if (shape1) *shape1 = e.shape1;
+  if (tasks_per_worker) *tasks_per_worker = e.tasks;
+  return HIDET_OK;
+}
+
+hidet_status_t hidet_taskmap_tasks(int32_t index, int32_t worker, int32_t* tasks_ij, int32_t capacity_pairs) {
+  if (index < 0 || index >= kNumTaskMaps || !tasks_ij) return HIDET_ERR_INVALID_ARG;
+  const TaskMapEntry& e = kTaskMaps[index];
+  if (worker < 0 || worker >= e.workers || capacity_pairs < e.tasks) return HIDET_ERR_INVALID_ARG;
+  for (int q = 0; q < e.tasks; ++q) {
+    const tmap::Task t = e.task(worker, q);
+    tasks_ij[2 * q] = t.i;
+    tasks_ij[2 * q + 1] = t.j;
+  }
+  return HIDET_OK;
+}
+
+hidet_status_t hidet_block_task(int32_t tiles_m, int32_t tiles_n, int32_t group, int32_t w, int32_t* tile_i,
+                                int32_t* tile_j) {
+  if (tiles_m <= 0 || tiles_n <= 0 || group <= 0 || w < 0 || w >= tiles_m * tiles_n || !tile_i || !tile_j)
+    return HIDET_ERR_INVALID_ARG;
+  const tmap::Task t = tmap::GroupedSpatial{tiles_m, tiles_n, group}.task(w);
+  *tile_i = t.i;
+  *tile_j = t.j;
+  return HIDET_OK;
+}
+
+const char* hidet_status_string(int32_t status) {
+  switch (status) {
+    case HIDET_OK: return "ok";
+    case HIDET_ERR_INVALID_ARG: return "invalid argument";
+    case HIDET_ERR_UNSUPPORTED: return "unsupported";
+    case HIDET_ERR_ALIGNMENT: return "misaligned pointer";
+    case HIDET_ERR_NO_CONFIG: return "no applicable tile configuration";
+    case HIDET_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+const char* hidet_version(void) { return "hidet-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -106,8 +106,10 @@ def conv_case(seed, Nb, IC, H, W, OC, KH, KW, stride, pad, dtype, bias=True, res
     x = normal(g, (Nb, IC, H, W), dtype)
     w = normal(g, (OC, IC, KH, KW), dtype, std=math.sqrt(2.0 / fan_in))
     b = normal(g, (OC,), dtype, std=0.1) if bias else None
-    OH = (H + 2 * pad - KH) // stride + 1
-    OW = (W + 2 * pad - KW) // stride + 1
+    sh, sw = stride if isinstance(stride, tuple) else (stride, stride)
+    ph, pw = pad if isinstance(pad, tuple) else (pad, pad)
+    OH = (H + 2 * ph - KH) // sh + 1
+    OW = (W + 2 * pw - KW) // sw + 1
     res = normal(g, (Nb, OC, OH, OW), dtype) if residual else None
     return dict(Nb=Nb, IC=IC, H=H, W=W, OC=OC, KH=KH, KW=KW, stride=stride, pad=pad, dtype=dtype, x=x, w=w, bias=b,
                 residual=res, OH=OH, OW=OW, seed=seed)

@@ -1,0 +1,103 @@
+"""Shared helpers of the GPU parity tests: host <-> device conversion and the comparison itself."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2210_09603_amd import binding as hb
+from paper_2210_09603_amd import workloads as wl
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}  # max relative Frobenius error (the stated parity bound)
+TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def output_rounding_floor(ref, dtype):
+    """Relative Frobenius error of the exact result rounded once (RNE) to the output dtype: no implementation
+    that emits `dtype` can do better.  For bf16 this floor is about 1.5e-3 on large tensors and fluctuates
+    above the 2e-3 bound on tensors of a few dozen elements."""
+    if dtype == "f32":
+        return 0.0
+    return oracle.rel_frobenius(wl.widen(wl.to_storage(ref.astype(np.float32), dtype), dtype), ref)
+
+
+def within_bound(err, ref, dtype):
+    """The parity bar: the stated bound, or (tiny bf16/fp16 outputs only) 10 % above the floor set by the
+    output rounding itself, whichever is larger."""
+    return err <= max(TOL[dtype], 1.1 * output_rounding_floor(ref, dtype) + 1e-5)
+
+
+def to_gpu(stored, dtype):
+    """Stored host array (workloads representation) -> GPU tensor with the same bits."""
+    if stored is None:
+        return None
+    if dtype == "bf16":
+        t = torch.from_numpy(np.ascontiguousarray(stored).view(np.int16)).view(torch.bfloat16)
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(stored))
+    return t.cuda()
+
+
+def to_f64(t):
+    """GPU tensor -> float64 numpy array (exact)."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def bias_axis_code(axis):
+    return {None: hb.HIDET_BIAS_NONE, "col": hb.HIDET_BIAS_PER_COL, "row": hb.HIDET_BIAS_PER_ROW}[axis]
+
+
+def oracle_bias_axis(axis):
+    return oracle.BIAS_PER_ROW if axis == "row" else oracle.BIAS_PER_COL
+
+
+def run_gemm_case(c, config=-1, relu=None, alpha=None):
+    """Run one workloads.gemm_case through the HIP path and the oracle; returns (rel_error, got, ref)."""
+    dt = c["dtype"]
+    relu = c.get("relu", False) if relu is None else relu
+    alpha = c.get("alpha", 1.0) if alpha is None else alpha
+    A, B = to_gpu(c["A"], dt), to_gpu(c["B"], dt)
+    M, N, K = c["M"], c["N"], c["K"]
+    Av = A[:, :M] if c["transA"] else A[:, :K]
+    Bv = B[:, :K] if c["transB"] else B[:, :N]
+    bias, res = to_gpu(c["bias"], dt), to_gpu(c["residual"], dt)
+    C = torch.full((M, N), float("nan"), dtype=TORCH_DTYPE[dt], device="cuda")
+    epi = hb.make_epilogue(alpha=alpha, bias=bias, bias_axis=bias_axis_code(c["bias_axis"]), residual=res, relu=relu)
+    hb.hidet_gemm(Av, Bv, C, transA=c["transA"], transB=c["transB"], epilogue=epi, config=config)
+    torch.cuda.synchronize()
+    A64 = wl.widen(c["A"], dt)
+    B64 = wl.widen(c["B"], dt)
+    A64 = A64[:, :M] if c["transA"] else A64[:, :K]
+    B64 = B64[:, :K] if c["transB"] else B64[:, :N]
+    ref = oracle.gemm(A64, B64, transA=c["transA"], transB=c["transB"], alpha=alpha,
+                      bias=None if c["bias"] is None else wl.widen(c["bias"], dt),
+                      bias_axis=oracle_bias_axis(c["bias_axis"]),
+                      residual=None if c["residual"] is None else wl.widen(c["residual"], dt), relu=relu)
+    got = to_f64(C)
+    return oracle.rel_frobenius(got, ref), got, ref
+
+
+def run_conv_case(c, config=-1):
+    dt = c["dtype"]
+    x, w = to_gpu(c["x"], dt), to_gpu(c["w"], dt)
+    bias, res = to_gpu(c["bias"], dt), to_gpu(c["residual"], dt)
+    stride, pad = (c["stride"], c["stride"]), (c["pad"], c["pad"])
+    if isinstance(c["stride"], tuple):
+        stride, pad = c["stride"], c["pad"]
+    y = torch.full(hb.conv_out_shape(x.shape, w.shape, stride, pad), float("nan"), dtype=TORCH_DTYPE[dt], device="cuda")
+    epi = hb.make_epilogue(alpha=c.get("alpha", 1.0), bias=bias, bias_axis=hb.HIDET_BIAS_PER_ROW, residual=res,
+                           relu=c.get("relu", False))
+    hb.hidet_conv2d_implicit_gemm(x, w, y, stride=stride, pad=pad, epilogue=epi, config=config)
+    torch.cuda.synchronize()
+    ref = oracle.conv2d(wl.widen(c["x"], dt), wl.widen(c["w"], dt), stride=stride, pad=pad, alpha=c.get("alpha", 1.0),
+                        bias=None if c["bias"] is None else wl.widen(c["bias"], dt),
+                        residual=None if c["residual"] is None else wl.widen(c["residual"], dt), relu=c.get("relu", False))
+    got = to_f64(y)
+    return oracle.rel_frobenius(got, ref), got, ref
+
+
+def applicable_configs(dtype):
+    out = []
+    for i in range(hb.hidet_config_count()):
+        info = hb.hidet_config_info(i)
+        if bool(info["is_f32"]) == (dtype == "f32"):
+            out.append(i)
+    return out

@@ -1,0 +1,252 @@
+"""Parity of the HIP path against the CPU oracle, element by element (relative Frobenius error)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2210_09603_amd import binding as hb
+from paper_2210_09603_amd import workloads as wl
+
+from helpers import TOL, TORCH_DTYPE, applicable_configs, run_conv_case, run_gemm_case, to_f64, to_gpu, within_bound
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ the benchmark configurations
+def test_config1_fp32_256():
+    (c,) = wl.config1()
+    err, _, _ = run_gemm_case(c)
+    _say("cfg1 err %.3e" % err)
+    assert err <= TOL["f32"]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_config2_transformer_mlp(dtype):
+    for c in wl.config2(dtype):
+        err, _, _ = run_gemm_case(c)
+        _say("%s %s err %.3e" % (c["name"], dtype, err))
+        assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_config3_resnet50_convs(dtype):
+    for c in wl.config3(dtype):
+        err, _, _ = run_conv_case(c)
+        _say("%s %s err %.3e" % (c["name"], dtype, err))
+        assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("batch,seq", [(12, 128), (12, 512), (192, 128)])
+def test_config4_attention_products(batch, seq):
+    c = wl.attention_case(4000 + batch + seq, batch, seq, "f16")
+    Q, K, V, S = (to_gpu(c[k], "f16") for k in ("Q", "K", "V", "S"))
+    scores = torch.full((batch, seq, seq), float("nan"), dtype=torch.float16, device="cuda")
+    hb.hidet_batched_gemm(Q, K, scores, transB=True, epilogue=hb.make_epilogue(alpha=c["alpha"]))
+    ctx = torch.full((batch, seq, c["d"]), float("nan"), dtype=torch.float16, device="cuda")
+    hb.hidet_batched_gemm(S, V, ctx)
+    torch.cuda.synchronize()
+    ref_s = oracle.batched_gemm(wl.widen(c["Q"], "f16"), wl.widen(c["K"], "f16"), transB=True, alpha=c["alpha"])
+    ref_c = oracle.batched_gemm(wl.widen(c["S"], "f16"), wl.widen(c["V"], "f16"))
+    got_s, got_c = to_f64(scores), to_f64(ctx)
+    worst = max(max(oracle.rel_frobenius(got_s[b], ref_s[b]) for b in range(batch)), oracle.rel_frobenius(got_s, ref_s),
+                max(oracle.rel_frobenius(got_c[b], ref_c[b]) for b in range(batch)), oracle.rel_frobenius(got_c, ref_c))
+    _say("cfg4 b%d s%d worst err %.3e" % (batch, seq, worst))
+    assert worst <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ sizes that are not multiples of anything
+ODD = [(1, 1, 1), (1, 17, 5), (17, 1, 33), (31, 33, 7), (127, 129, 65), (257, 63, 130), (64, 64, 64), (200, 300, 72)]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, False), (True, True)])
+def test_odd_shapes(dtype, transA, transB):
+    for i, (M, N, K) in enumerate(ODD):
+        c = wl.gemm_case(7000 + i, M, N, K, dtype, transA=transA, transB=transB, bias="col", residual=(i % 2 == 0))
+        err, _, ref = run_gemm_case(c, relu=(i % 3 == 0), alpha=0.5)
+        _say("odd %s tA%d tB%d %dx%dx%d err %.3e" % (dtype, transA, transB, M, N, K, err))
+        assert within_bound(err, ref, dtype), (M, N, K)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_padded_leading_dimensions_keep_vector_loads(dtype):
+    # leading dimensions that are multiples of 16 bytes but larger than the rows: the vector path with K and N tails
+    c = wl.gemm_case(7100, 150, 203, 77, dtype, bias="row", lda_pad=83 - 77 + 5, ldb_pad=5)
+    assert c["lda"] % 8 == 0 and c["ldb"] % 8 == 0
+    err, _, _ = run_gemm_case(c, relu=True)
+    assert err <= TOL[dtype]
+
+
+def test_prime_size_2039():
+    # the size on which input-centric schedule spaces have no valid schedule (Section 3.3)
+    c = wl.gemm_case(7200, 2039, 2039, 2039, "f16", bias="col")
+    err, _, _ = run_gemm_case(c, relu=True)
+    _say("2039^3 err %.3e" % err)
+    assert err <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ every configuration of the schedule space
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_every_config_on_an_odd_shape(dtype):
+    for cfg in applicable_configs(dtype):
+        for tB in (False, True):
+            c = wl.gemm_case(7300 + cfg, 283, 331, 203, dtype, transB=tB, bias="col", residual=True)
+            err, _, _ = run_gemm_case(c, config=cfg, relu=True, alpha=0.75)
+            _say("config %d %s tB%d err %.3e" % (cfg, dtype, tB, err))
+            assert err <= TOL[dtype], cfg
+        # aligned variant (vector loads) of the same configuration
+        c = wl.gemm_case(7400 + cfg, 264, 328, 200, dtype, bias="row")
+        err, _, _ = run_gemm_case(c, config=cfg)
+        assert err <= TOL[dtype], cfg
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_every_config_conv(dtype):
+    for cfg in applicable_configs(dtype):
+        c = wl.conv_case(7500 + cfg, 2, 5, 11, 9, 7, 3, 3, 2, 1, dtype, residual=True)
+        c.update(relu=True)
+        err, _, _ = run_conv_case(c, config=cfg)
+        _say("conv config %d %s err %.3e" % (cfg, dtype, err))
+        assert err <= TOL[dtype], cfg
+
+
+# ------------------------------------------------------------------ epilogue flags, all 8 combinations
+@pytest.mark.parametrize("flags", range(8))
+def test_epilogue_flag_combinations(flags):
+    c = wl.gemm_case(7600 + flags, 96, 136, 72, "f16", bias="col" if flags & 1 else None, residual=bool(flags & 2))
+    err, got, _ = run_gemm_case(c, relu=bool(flags & 4), alpha=1.0 if flags < 4 else 0.125)
+    assert err <= TOL["f16"]
+    if flags & 4:
+        assert got.min() >= 0.0
+
+
+def test_identity_epilogue_and_closed_forms():
+    # all-ones contraction: every output equals K exactly (fp16 holds 1..2048 exactly)
+    for K in (1, 64, 100, 2048):
+        A = torch.ones((70, K), dtype=torch.float16, device="cuda")
+        B = torch.ones((K, 90), dtype=torch.float16, device="cuda")
+        C = torch.zeros((70, 90), dtype=torch.float16, device="cuda")
+        hb.hidet_gemm(A, B, C)
+        assert torch.all(C == K)
+    eye = torch.eye(96, dtype=torch.float32, device="cuda")
+    X = torch.randn(96, 96, device="cuda")
+    C = torch.zeros_like(X)
+    hb.hidet_gemm(X, eye, C)
+    assert torch.equal(C, X)
+
+
+# ------------------------------------------------------------------ convolution prologue variants
+CONVS = [
+    # Nb, IC, H, W, OC, KH, KW, stride, pad
+    (1, 3, 8, 8, 4, 1, 1, 1, 0),
+    (1, 8, 14, 14, 16, 3, 3, 1, 1),
+    (2, 16, 9, 7, 5, 3, 3, 2, 1),
+    (3, 4, 12, 12, 9, 5, 5, 1, 2),
+    (1, 256, 28, 28, 32, 3, 3, 2, 1),  # the strided layer of the paper's schedule-space study (fewer output channels)
+    (2, 7, 10, 10, 3, 2, 2, 2, 0),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_conv_shapes(dtype):
+    for i, (Nb, IC, H, W, OC, KH, KW, s, p) in enumerate(CONVS):
+        c = wl.conv_case(7700 + i, Nb, IC, H, W, OC, KH, KW, s, p, dtype, residual=(i % 2 == 1))
+        c.update(relu=(i % 2 == 0))
+        err, _, _ = run_conv_case(c)
+        _say("conv %s %s err %.3e" % (dtype, CONVS[i], err))
+        assert err <= TOL[dtype], CONVS[i]
+
+
+def test_conv_rectangular_stride_and_padding():
+    c = wl.conv_case(7800, 2, 6, 13, 10, 8, 3, 2, (2, 1), (0, 1), "f16")
+    c.update(relu=True)
+    err, _, _ = run_conv_case(c)
+    assert err <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ degenerate cases and argument checking on the device
+def test_empty_and_k0():
+    A = torch.zeros((0, 8), dtype=torch.float16, device="cuda")
+    B = torch.zeros((8, 5), dtype=torch.float16, device="cuda")
+    C = torch.zeros((0, 5), dtype=torch.float16, device="cuda")
+    hb.hidet_gemm(A, B, C)  # no-op
+    # K = 0: C = epilogue(0)
+    bias = torch.tensor([1.0, -2.0, 3.0], dtype=torch.float16, device="cuda")
+    C = torch.full((4, 3), float("nan"), dtype=torch.float16, device="cuda")
+    hb.hidet_gemm(torch.zeros((4, 0), dtype=torch.float16, device="cuda"),
+                  torch.zeros((0, 3), dtype=torch.float16, device="cuda"), C,
+                  epilogue=hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True))
+    torch.cuda.synchronize()
+    assert torch.equal(C.cpu(), torch.tensor([[1.0, 0.0, 3.0]] * 4, dtype=torch.float16))
+
+
+def test_output_outside_the_problem_is_untouched():
+    c = wl.gemm_case(7900, 45, 51, 40, "f16")
+    A, B = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16")
+    big = torch.full((64, 64), 7.0, dtype=torch.float16, device="cuda")
+    hb.hidet_gemm(A, B, big[:45, :51])
+    torch.cuda.synchronize()
+    assert torch.all(big[45:, :] == 7.0) and torch.all(big[:, 51:] == 7.0)
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"))
+    assert oracle.rel_frobenius(to_f64(big[:45, :51]), ref) <= TOL["f16"]
+
+
+def test_misaligned_pointers_use_element_loads():
+    c = wl.gemm_case(7950, 65, 70, 50, "f16")
+    buf_a = torch.zeros(65 * 50 + 1, dtype=torch.float16, device="cuda")
+    buf_b = torch.zeros(50 * 70 + 3, dtype=torch.float16, device="cuda")
+    buf_c = torch.zeros(65 * 70 + 1, dtype=torch.float16, device="cuda")
+    A = buf_a[1:].view(65, 50)
+    B = buf_b[3:].view(50, 70)
+    C = buf_c[1:].view(65, 70)
+    A.copy_(to_gpu(c["A"], "f16"))
+    B.copy_(to_gpu(c["B"], "f16"))
+    hb.hidet_gemm(A, B, C)
+    torch.cuda.synchronize()
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"))
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+
+
+def test_batched_with_shared_operand_and_residual():
+    g = wl.rng(8000)
+    A = wl.normal(g, (5, 33, 40), "f16")
+    B = wl.normal(g, (40, 29), "f16")  # shared by the batch (stride 0)
+    R = wl.normal(g, (5, 33, 29), "f16")
+    dA, dB, dR = to_gpu(A, "f16"), to_gpu(B, "f16"), to_gpu(R, "f16")
+    C = torch.zeros((5, 33, 29), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(residual=dR, relu=True, batched=True)
+    hb.hidet_batched_gemm(dA, dB.unsqueeze(0).expand(5, 40, 29), C, epilogue=epi)
+    torch.cuda.synchronize()
+    ref = oracle.batched_gemm(wl.widen(A, "f16"), np.broadcast_to(wl.widen(B, "f16"), (5, 40, 29)),
+                              residual=wl.widen(R, "f16"), relu=True)
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ tuning
+def test_tuner_enumerates_the_space_and_caches(tmp_path):
+    c = wl.gemm_case(8100, 128, 768, 256, "f16", bias="col")
+    A, B, bias = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16"), to_gpu(c["bias"], "f16")
+    C = torch.zeros((128, 768), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True)
+    hb.hidet_tune_clear()
+    best, us = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=5)
+    times = hb.hidet_tune_last_times()
+    ok = [i for i, t in enumerate(times) if t > 0]
+    assert sorted(ok) == applicable_configs("f16")
+    assert best in ok and abs(times[best] - us) < 1e-3 and us == min(times[i] for i in ok)
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"), bias=wl.widen(c["bias"], "f16"), relu=True)
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+    path = str(tmp_path / "tuned.txt")
+    hb.hidet_tune_save(path)
+    text = open(path).read()
+    assert "gemm:t1:00:b1:128x768x256" in text and text.strip().endswith(str(best))
+    hb.hidet_tune_clear()
+    hb.hidet_tune_load(path)
+    C.zero_()
+    hb.hidet_gemm(A, B, C, epilogue=epi)
+    torch.cuda.synchronize()
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]

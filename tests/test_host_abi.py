@@ -1,0 +1,158 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, validates its
+arguments before touching the GPU, and its compile-time task mappings equal the paper's definitions."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import taskmap as otm
+from paper_2210_09603_amd import binding as hb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hidet_mi355x.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hidet_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = hb.lib()
+    names = _declared_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(hb.EXPORTS) == names
+
+
+def test_version_and_schedule_space():
+    assert "gfx950" in hb.hidet_version()
+    n = hb.hidet_config_count()
+    assert 10 <= n < 200  # "less than 200 schedules" (Section 4.3)
+    seen = set()
+    for i in range(n):
+        c = hb.hidet_config_info(i)
+        waves = c["waves_m"] * c["waves_n"]
+        assert c["mfma"] in (16, 32) and 1 <= waves <= 16
+        assert c["block_m"] % (c["waves_m"] * c["mfma"]) == 0 and c["block_n"] % (c["waves_n"] * c["mfma"]) == 0
+        assert c["lds_bytes"] <= 160 * 1024  # LDS of one compute unit
+        # accumulators: one fp32 register per output element per lane, at most 256 of the 512 registers
+        assert c["block_m"] * c["block_n"] // (waves * 64) <= 256
+        key = tuple(c.values())
+        assert key not in seen
+        seen.add(key)
+    with pytest.raises(hb.HidetError):
+        hb.hidet_config_info(n)
+
+
+def _gemm(L, **kw):
+    a = dict(config=-1, i=hb.HIDET_F16, o=hb.HIDET_F16, tA=0, tB=0, M=8, N=8, K=8, A=0x1000, lda=8, B=0x2000, ldb=8,
+             C=0x3000, ldc=8, epi=None, stream=None)
+    a.update(kw)
+    return L.hidet_gemm_cfg(a["config"], a["i"], a["o"], a["tA"], a["tB"], a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"],
+                            a["ldb"], a["C"], a["ldc"], a["epi"], a["stream"])
+
+
+def test_gemm_argument_validation_happens_before_any_launch():
+    """All pointers below are fake: reaching a launch would fault, so every call must be rejected on the host."""
+    L = hb.lib()
+    INVALID, UNSUPPORTED, ALIGN, NOCFG = 1, 2, 3, 4
+    assert _gemm(L, A=None) == INVALID
+    assert _gemm(L, C=None) == INVALID
+    assert _gemm(L, M=-1) == INVALID
+    assert _gemm(L, lda=7) == INVALID
+    assert _gemm(L, ldb=7) == INVALID
+    assert _gemm(L, ldc=7) == INVALID
+    assert _gemm(L, tA=1, M=16, lda=8) == INVALID  # transposed A is K x M: lda >= M
+    assert _gemm(L, i=7) == INVALID
+    assert _gemm(L, i=hb.HIDET_F16, o=hb.HIDET_F32) == UNSUPPORTED
+    assert _gemm(L, M=2 ** 31) == UNSUPPORTED
+    assert _gemm(L, A=0x1001) == ALIGN
+    assert _gemm(L, i=hb.HIDET_F32, o=hb.HIDET_F32, C=0x3002) == ALIGN
+    assert _gemm(L, config=10 ** 6) == NOCFG
+    # an fp32-only configuration cannot run an fp16 problem
+    f32_cfg = [i for i in range(hb.hidet_config_count()) if hb.hidet_config_info(i)["is_f32"]][0]
+    assert _gemm(L, config=f32_cfg) == NOCFG
+    e = hb.hidet_epilogue_t()
+    e.struct_size = 4
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.struct_size = ctypes.sizeof(hb.hidet_epilogue_t)
+    e.bias_axis = hb.HIDET_BIAS_PER_COL  # bias axis without a bias pointer
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.bias_axis = 0
+    e.residual = 0x5000
+    e.ld_residual = 4
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.ld_residual = 8
+    e.act = 9
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    # empty problems are OK no-ops even with null pointers
+    assert _gemm(L, M=0, A=None, B=None, C=None) == 0
+    assert _gemm(L, N=0, A=None, B=None, C=None) == 0
+
+
+def test_batched_and_conv_argument_validation():
+    L = hb.lib()
+    f16 = hb.HIDET_F16
+    # overlapping batch entries of C
+    assert L.hidet_batched_gemm(f16, f16, 0, 0, 4, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 32, None, None) == 1
+    assert L.hidet_batched_gemm(f16, f16, 0, 0, -1, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 64, None, None) == 1
+    assert L.hidet_batched_gemm(f16, f16, 0, 0, 0, 8, 8, 8, None, 8, 64, None, 8, 64, None, 8, 64, None, None) == 0
+    conv = lambda **k: L.hidet_conv2d_implicit_gemm(
+        k.get("i", f16), k.get("o", f16), k.get("Nb", 1), k.get("IC", 4), k.get("H", 8), k.get("W", 8), k.get("OC", 4),
+        k.get("KH", 3), k.get("KW", 3), k.get("sh", 1), k.get("sw", 1), k.get("ph", 1), k.get("pw", 1), k.get("x", 0x1000),
+        k.get("w", 0x2000), k.get("y", 0x3000), k.get("epi", None), None)
+    assert conv(x=None) == 1
+    assert conv(sh=0) == 1
+    assert conv(KH=0) == 1
+    assert conv(ph=-1) == 1
+    assert conv(y=0x3001) == 3
+    assert conv(H=1, W=1, KH=5, KW=5, ph=0, pw=0, x=None, w=None, y=None) == 0  # empty output
+    e = hb.hidet_epilogue_t()
+    e.struct_size = ctypes.sizeof(hb.hidet_epilogue_t)
+    e.bias = 0x4000
+    e.bias_axis = hb.HIDET_BIAS_PER_COL  # conv bias is per output channel = per GEMM row
+    assert conv(epi=ctypes.byref(e)) == 1
+    assert hb.lib().hidet_status_string(3) == b"misaligned pointer"
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(hb, "_lib", None)
+    monkeypatch.setattr(hb, "LIB_PATH", "/nonexistent/libhidet_mi355x.so")
+    with pytest.raises(RuntimeError, match="HIP extension missing"):
+        hb.lib()
+
+
+# ---------------------------------------------------------------- task mappings: templates == definitions
+def _parse(expr):
+    f = None
+    for term in expr.split("*"):
+        m = re.fullmatch(r"(repeat|spatial)\((\d+),(\d+)\)", term.strip())
+        g = getattr(otm, m.group(1))(int(m.group(2)), int(m.group(3)))
+        f = g if f is None else f * g
+    return f
+
+
+def test_compile_time_task_mappings_match_the_definitions():
+    n = hb.hidet_taskmap_count()
+    assert n >= 8
+    for idx in range(n):
+        info = hb.hidet_taskmap_info(idx)
+        ref = _parse(info["expr"])
+        assert info["workers"] == ref.num_workers and info["shape"] == ref.task_shape, info
+        for w in range(ref.num_workers):
+            assert hb.hidet_taskmap_tasks(idx, w) == ref(w), (info["expr"], w)
+
+
+def test_block_level_mapping_is_a_permutation_and_groups_rows():
+    for tiles_m, tiles_n, group in [(16, 16, 4), (5, 7, 4), (1, 9, 1), (3, 3, 8), (7, 2, 4)]:
+        tasks = [hb.hidet_block_task(tiles_m, tiles_n, group, w) for w in range(tiles_m * tiles_n)]
+        assert sorted(tasks) == [(i, j) for i in range(tiles_m) for j in range(tiles_n)]
+    # 16x16 tiles, group 4: any 32 consecutive workgroups (one die's share) cover a 4 x 8 patch
+    tasks = [hb.hidet_block_task(16, 16, 4, w) for w in range(256)]
+    for s in range(0, 256, 32):
+        rows = {t[0] for t in tasks[s:s + 32]}
+        cols = {t[1] for t in tasks[s:s + 32]}
+        assert len(rows) == 4 and len(cols) == 8
