@@ -71,7 +71,7 @@ typedef struct {
  * transA == 0: A is stored M x K (lda >= K); transA != 0: A is stored K x M (lda >= M).
  * transB == 0: B is stored K x N (ldb >= N); transB != 0: B is stored N x K (ldb >= K).
  * `in` is the dtype of A and B, `out` the dtype of C, bias and residual.  Supported pairs:
- * (F32,F32), (F16,F16), (F16,F32), (BF16,BF16), (BF16,F32).
+ * (F32,F32), (F16,F16), (BF16,BF16); any other pair returns HIDET_ERR_UNSUPPORTED.
  * The tile configuration is the cached tuning winner for this problem if hidet_tune_gemm has
  * seen it, otherwise a size-based default.
  */
@@ -131,7 +131,10 @@ typedef struct {
   int32_t waves_m, waves_n;          /* wavefront grid inside the workgroup: spatial(waves_m, waves_n) */
   int32_t mfma;                      /* matrix-core tile edge: 32 (32x32xk) or 16 (16x16xk) */
   int32_t is_f32;                    /* 1: configuration for fp32 inputs, 0: for fp16/bf16 inputs */
-  int32_t lds_bytes;                 /* LDS used by the two staging buffers */
+  int32_t schedule;                  /* 0: two LDS stages, next tile staged through registers;
+                                        1: ring of four stages filled by direct global -> LDS loads, wavefront ping-pong */
+  int32_t stages;                    /* LDS stages of block_k each */
+  int32_t lds_bytes;                 /* LDS allocated by the workgroup */
 } hidet_config_info_t;
 int32_t hidet_config_count(void);
 hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info);

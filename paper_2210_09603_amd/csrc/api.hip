@@ -20,8 +20,8 @@ using namespace hidet;
 // ------------------------------------------------------------------------------------------------
 #define HIDET_ALL
 static const ConfigRow kConfigs[] = {
-#define X16(idx, BM, BN, BK, WM, WN, MI, TA) {idx, BM, BN, BK, WM, WN, MI, TA, 0},
-#define X32(idx, BM, BN, BK, WM, WN, MI, TA) {idx, BM, BN, BK, WM, WN, MI, TA, 1},
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA, SC) {idx, BM, BN, BK, WM, WN, MI, TA, SC, 0},
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA, SC) {idx, BM, BN, BK, WM, WN, MI, TA, SC, 1},
 #include "configs.def"
 #undef X16
 #undef X32
@@ -29,10 +29,10 @@ static const ConfigRow kConfigs[] = {
 static const int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
 // weak: a development build may leave some (configuration, type) objects out; their table slots stay empty
-#define X16(idx, BM, BN, BK, WM, WN, MI, TA)                                    \
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA, SC)                                  \
   extern "C" void hidet_register_##idx##_1(Registry*) __attribute__((weak));    \
   extern "C" void hidet_register_##idx##_2(Registry*) __attribute__((weak));
-#define X32(idx, BM, BN, BK, WM, WN, MI, TA) extern "C" void hidet_register_##idx##_0(Registry*) __attribute__((weak));
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA, SC) extern "C" void hidet_register_##idx##_0(Registry*) __attribute__((weak));
 #include "configs.def"
 #undef X16
 #undef X32
@@ -41,10 +41,10 @@ static const Registry& registry() {
   static Registry* r = [] {
     Registry* reg = new Registry();
     std::memset(reg, 0, sizeof(Registry));
-#define X16(idx, BM, BN, BK, WM, WN, MI, TA)                  \
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA, SC)                \
   if (hidet_register_##idx##_1) hidet_register_##idx##_1(reg); \
   if (hidet_register_##idx##_2) hidet_register_##idx##_2(reg);
-#define X32(idx, BM, BN, BK, WM, WN, MI, TA) \
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA, SC) \
   if (hidet_register_##idx##_0) hidet_register_##idx##_0(reg);
 #include "configs.def"
 #undef X16
@@ -76,6 +76,7 @@ struct Problem {
 int elem_size(int dtype) { return dtype == HIDET_F32 ? 4 : 2; }
 bool aligned(const void* ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; }
 constexpr long long kIntMax = 2147483647LL;
+constexpr long long kMaxVecLd = 4LL << 20;  // in-tile element offsets (row * ld + col, row < 256) stay below 2^31
 
 hidet_status_t check_dtypes(int in, int out) {
   if (in < 0 || in > 2 || out < 0 || out > 2) return HIDET_ERR_INVALID_ARG;
@@ -159,8 +160,10 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
   p.strideC = strideC;
   fill_epilogue(p, epi);
   const int vec = 16 / elem_size(in);
-  const bool a_vec = aligned(A, 16) && lda % vec == 0 && strideA % vec == 0;
-  const bool b_vec = aligned(B, 16) && ldb % vec == 0 && strideB % vec == 0;
+  // vector loads need 16-byte aligned rows, no chunk straddling a matrix edge, and 32-bit in-tile offsets
+  const long long a_contig = transA ? M : K, b_contig = transB ? K : N;
+  const bool a_vec = aligned(A, 16) && lda % vec == 0 && strideA % vec == 0 && a_contig % vec == 0 && lda <= kMaxVecLd;
+  const bool b_vec = aligned(B, 16) && ldb % vec == 0 && strideB % vec == 0 && b_contig % vec == 0 && ldb <= kMaxVecLd;
   pr.elem_mode = (a_vec && b_vec) ? 0 : 1;
   const size_t va = 4 * (size_t)elem_size(out);
   bool vs = aligned(C, va) && ldc % 4 == 0 && strideC % 4 == 0;
@@ -219,7 +222,7 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   p.out_inner = OH * OW;
   p.out_outer = OC * OH * OW;
   const int vec = 16 / elem_size(in);
-  pr.elem_mode = (aligned(w, 16) && K % vec == 0) ? 0 : 1;
+  pr.elem_mode = (aligned(w, 16) && K % vec == 0 && K <= kMaxVecLd) ? 0 : 1;
   const size_t va = 4 * (size_t)elem_size(out);
   bool vs = aligned(y, va) && p.out_inner % 4 == 0;
   if (p.residual) vs = vs && aligned(p.residual, va);
@@ -454,7 +457,11 @@ hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info) {
   info->waves_n = r.waves_n;
   info->mfma = r.mfma;
   info->is_f32 = r.is_f32;
-  info->lds_bytes = 2 * (r.bm + r.bn) * r.bk * (r.is_f32 ? 4 : 2);
+  info->schedule = r.sched;
+  info->stages = r.sched == 1 ? 4 : 2;
+  const int staging = info->stages * (r.bm + r.bn) * r.bk * (r.is_f32 ? 4 : 2);
+  const int epilogue = r.waves_m * r.mfma * (r.bn * 4 + 16 * r.waves_n);  // per-wave transposition regions
+  info->lds_bytes = staging > epilogue ? staging : epilogue;
   return HIDET_OK;
 }
 

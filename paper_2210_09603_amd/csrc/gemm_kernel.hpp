@@ -8,6 +8,10 @@
 //           img2col gather) are fused here: they only change how an element's address is formed.
 //   step 3  double buffering: the next tile travels global -> registers while the matrix cores
 //           work on the current LDS buffer, and is written to the other buffer afterwards
+//           (gemm_kernel).  The large-tile schedule (gemm_kernel_pingpong) goes further: a ring
+//           of four LDS stages filled by direct global -> LDS loads three stages ahead, and the
+//           two wavefronts of every SIMD half a step apart, one on the matrix cores while the
+//           other reads LDS.
 //   step 4  wave-level task mapping spatial(WAVES_M, WAVES_N) o repeat(FM, FN) of MFMA tiles,
 //           fp32 accumulators in registers
 //   step 5  fused epilogue on the accumulators (alpha, bias, residual, ReLU, cast) and predicated
@@ -43,6 +47,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 enum : int { L_KC = 0, L_MC = 1 };                    // operand contiguity
 enum : int { LD_VEC = 0, LD_ELEM = 1, LD_IM2COL = 2 };  // how a chunk is fetched from global memory
 enum : int { MAP_PLAIN = 0, MAP_NCHW = 1 };           // output index map
+enum : int { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1 };  // main-loop schedule
 
 struct ConvGeom {
   int IC, H, W, KH, KW, sh, sw, ph, pw, OH, OW;
@@ -83,11 +88,14 @@ __device__ __forceinline__ constexpr int swz_kc(int row) {
   if constexpr (CPR == 4) return ((row >> 1) & 3) ^ ((row >> 3) & 1);
   return 0;
 }
-template <int CPR>
+template <int CPR, int MI>
 __device__ __forceinline__ constexpr int swz_mc(int k) {
-  if constexpr (CPR >= 16) {
-    const int t = k & 3;
-    return t == 0 ? 0 : (t == 1 ? 6 : (t == 2 ? 10 : 12));
+  if constexpr (CPR >= 16 && MI == 32) {
+    return (0xCA60 >> (4 * (k & 3))) & 15;  // k % 4 -> 0, 6, 10, 12 (a lookup packed into one constant)
+  }
+  if constexpr (CPR >= 16 && MI == 16) {
+    // one 16x16 transposing read touches k rows kb..kb+3 and kb+8..kb+11 in the same cycle
+    return 2 * ((k & 3) | (((k >> 3) & 1) << 2));
   }
   if constexpr (CPR == 8) return (k & 3) * 2;
   if constexpr (CPR == 4) return ((k >> 1) & 1) * 2;
@@ -155,12 +163,12 @@ __device__ __forceinline__ TO from_f32(float v) {
 // Tile configuration: everything the template needs, plus derived constants.
 // ---------------------------------------------------------------------------------------------
 template <typename T_, typename TO_, int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int MI_, int LA_, int LB_,
-          int MODE_A_, int MODE_B_, int MAPPER_>
+          int MODE_A_, int MODE_B_, int MAPPER_, int SCHED_ = SCHED_SIMPLE>
 struct GemmConfig {
   using T = T_;
   using TO = TO_;
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, MI = MI_;
-  static constexpr int LA = LA_, LB = LB_, MODE_A = MODE_A_, MODE_B = MODE_B_, MAPPER = MAPPER_;
+  static constexpr int LA = LA_, LB = LB_, MODE_A = MODE_A_, MODE_B = MODE_B_, MAPPER = MAPPER_, SCHED = SCHED_;
   static constexpr bool IS_F32 = sizeof(T) == 4;
   static constexpr int VEC = 16 / (int)sizeof(T);
   static constexpr int NWAVES = WAVES_M * WAVES_N;
@@ -173,7 +181,10 @@ struct GemmConfig {
   static constexpr int A_BYTES = BM * BK * (int)sizeof(T);
   static constexpr int B_BYTES = BN * BK * (int)sizeof(T);
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static constexpr int STAGES = (SCHED == SCHED_PINGPONG) ? 4 : 2;
+  // per-wave transposition regions of the epilogue: MI rows of the wave tile in fp32, rows padded by 16 bytes
+  static constexpr int EPI_BYTES = NWAVES * MI * (WTN * 4 + 16);
+  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
   static constexpr int NL_A = BM * BK / VEC / NT;  // chunks per thread per tile
   static constexpr int NL_B = BN * BK / VEC / NT;
   static_assert(BM % (WAVES_M * MI) == 0 && BN % (WAVES_N * MI) == 0, "wave tiles must be whole MFMA tiles");
@@ -291,25 +302,86 @@ struct Operand {
     return __builtin_bit_cast(u32x4, tmp);
   }
 
-  __device__ __forceinline__ void load(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
+  // Vector mode (LD_VEC): the host guarantees 16-byte aligned rows and that no chunk straddles the
+  // edge of the matrix (K, resp. the M/N extent, is a multiple of the chunk length).  Chunks that lie
+  // outside the matrix along M/N are redirected to the last valid row / chunk: they only feed output
+  // rows or columns that are never stored, so any finite or non-finite value is harmless there.
+  // Along K a chunk outside the matrix must read as zero; that can only happen in the last K tile.
+  int off[NL];  // element offset of each chunk from `src` at k = 0 (vector mode only)
+
+  __device__ __forceinline__ void init(int tid) {
+    if constexpr (MODE == LD_VEC) {
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        const int sr = t.i, sc = t.j * VEC;
+        if constexpr (LAYOUT == L_KC) {
+          const int r = sr < rows_left ? sr : rows_left - 1;
+          off[q] = r * (int)ld + sc;
+        } else {
+          const int c = sc + VEC <= rows_left ? sc : rows_left - VEC;
+          off[q] = sr * (int)ld + c;
+        }
+      }
+    }
+  }
+
+  // Direct global -> LDS loads (vector mode, 16-bit types).  Lane l of a wave writes its 16 bytes at
+  // LDS[base + 16*l], so the LDS side of the cooperative load is fixed -- thread t's q-th load fills
+  // stored position q*NT + t of the tile -- and the swizzle moves to the global side: the thread
+  // fetches the logical chunk that belongs at that position.  The instruction is issued through
+  // inline assembly and tracked by hand with s_waitcnt vmcnt(n): the schedule that uses it keeps
+  // several stages in flight and waits for the oldest only.
+  int doff[NL];
+  __device__ __forceinline__ void init_direct(int tid) {
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const int pos = q * NT + tid;
+      const int row = pos / CPR, pc = pos % CPR;
+      const int lc = pc ^ ((LAYOUT == L_KC) ? swz_kc<CPR>(row) : swz_mc<CPR, MI>(row));
+      if constexpr (LAYOUT == L_KC) {
+        const int r = row < rows_left ? row : rows_left - 1;
+        doff[q] = r * (int)ld + lc * VEC;
+      } else {
+        const int c = lc * VEC + VEC <= rows_left ? lc * VEC : rows_left - VEC;
+        doff[q] = row * (int)ld + c;
+      }
+    }
+  }
+  // `tile_lds`: LDS byte address of the tile; `wave`: wave index (both wave-uniform).
+  __device__ __forceinline__ void load_direct(unsigned tile_lds, int wave, int k0) const {
+    const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const T* g = base + doff[q];
+      const unsigned dst = tile_lds + (unsigned)((q * NT + wave * 64) * 16);
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst) : "memory");
+    }
+  }
+
+  // A K tile that lies entirely inside the matrix: no predicates at all in vector mode.
+  __device__ __forceinline__ void load_full(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
+    if constexpr (MODE == LD_VEC) {
+      const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+#pragma unroll
+      for (int q = 0; q < NL; ++q) regs[q] = *reinterpret_cast<const u32x4*>(base + off[q]);
+    } else {
+      load_edge(regs, tid, k0, g);
+    }
+  }
+
+  // The last, partial K tile (and every tile of the element-wise modes).
+  __device__ __forceinline__ void load_edge(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
       const int sr = t.i, sc = t.j * VEC;  // stored row, first stored column of the chunk
       if constexpr (MODE == LD_VEC) {
-        bool full;
-        const T* ptr;
-        if constexpr (LAYOUT == L_KC) {
-          full = (sr < rows_left) && (k0 + sc + VEC <= K);
-          ptr = src + (long long)sr * ld + (k0 + sc);
-        } else {
-          full = (k0 + sr < K) && (sc + VEC <= rows_left);
-          ptr = src + (long long)(k0 + sr) * ld + sc;
-        }
-        if (full)
-          regs[q] = *reinterpret_cast<const u32x4*>(ptr);
-        else
-          regs[q] = gather(sr, sc, k0, g);
+        const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+        const bool inside = (LAYOUT == L_KC) ? (k0 + sc < K) : (k0 + sr < K);
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (inside) v = *reinterpret_cast<const u32x4*>(base + off[q]);
+        regs[q] = v;
       } else {
         regs[q] = gather(sr, sc, k0, g);
       }
@@ -322,7 +394,7 @@ struct Operand {
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
       if constexpr (!IS_F32) {
-        const int swz = (LAYOUT == L_KC) ? swz_kc<CPR>(t.i) : swz_mc<CPR>(t.i);
+        const int swz = (LAYOUT == L_KC) ? swz_kc<CPR>(t.i) : swz_mc<CPR, MI>(t.i);
         *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = regs[q];
       } else if constexpr (LAYOUT == L_MC) {
         *reinterpret_cast<u32x4*>(tile + (t.i * CPR + t.j) * 16) = regs[q];
@@ -365,7 +437,7 @@ struct Operand {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int kk = k + 4 * i;
-        const unsigned char* addr = tile + (kk * CPR + ((col / 8) ^ swz_mc<CPR>(kk))) * 16 + (col % 8) * 2;
+        const unsigned char* addr = tile + (kk * CPR + ((col / 8) ^ swz_mc<CPR, MI>(kk))) * 16 + (col % 8) * 2;
         const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
             (__attribute__((address_space(3))) i16x4*)(const_cast<unsigned char*>(addr)));
         h[i] = __builtin_bit_cast(u32x2, v);
@@ -381,7 +453,8 @@ struct Operand {
 // ---------------------------------------------------------------------------------------------
 template <typename TO, int MAPPER>
 __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, const TO* __restrict__ R,
-                                       const TO* __restrict__ bias, int m, int n, const float (&acc)[4]) {
+                                       const TO* __restrict__ bias, const float (&col_bias)[4], int m, int n,
+                                       const float (&acc)[4]) {
   if (m >= p.M || n >= p.N) return;
   long long off, roff;
   if constexpr (MAPPER == MAP_PLAIN) {
@@ -400,10 +473,9 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     const float b = to_f32(bias[m]);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] += b;
-  } else if (p.bias_axis == 1) {
+  } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (n + e < p.N) v[e] += to_f32(bias[n + e]);
+    for (int e = 0; e < 4; ++e) v[e] += col_bias[e];  // zeros unless the bias is per column
   }
   if (R != nullptr) {
     if (whole) {
@@ -456,12 +528,123 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// The kernel.
+// Pieces shared by the kernels.
+// ---------------------------------------------------------------------------------------------
+struct BlockCoords {
+  int batch, m0, n0;
+};
+
+// Step 1, block-level task mapping.  Workgroups are handed to the 8 accelerator dies (XCDs)
+// round-robin; they are renumbered so that each die, which has a private L2, works on one
+// contiguous run of tiles of the grouped traversal.
+template <int BM, int BN>
+__device__ __forceinline__ BlockCoords block_coords(const GemmParams& p) {
+  const int total = p.total_blocks;
+  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  const int per = total / 8, extra = total % 8;
+  const int logical = xcd * per + (xcd < extra ? xcd : extra) + slot;
+  const int tiles = p.tiles_m * p.tiles_n;
+  const int batch = logical / tiles;
+  const tmap::Task tile = tmap::GroupedSpatial{p.tiles_m, p.tiles_n, p.group}.task(logical - batch * tiles);
+  return BlockCoords{batch, tile.i * BM, tile.j * BN};
+}
+
+template <class Cfg, class OpA, class OpB>
+__device__ __forceinline__ void setup_operands(const GemmParams& p, const BlockCoords& bc, OpA& opa, OpB& opb) {
+  using T = typename Cfg::T;
+  const T* A = reinterpret_cast<const T*>(p.A) + (long long)bc.batch * p.strideA;
+  const T* B = reinterpret_cast<const T*>(p.B) + (long long)bc.batch * p.strideB;
+  opa.src = (Cfg::LA == L_KC) ? A + (long long)bc.m0 * p.lda : A + bc.m0;
+  opa.ld = p.lda;
+  opa.rows_left = p.M - bc.m0;
+  opa.K = p.K;
+  opa.r0 = bc.m0;
+  if constexpr (Cfg::MODE_B == LD_IM2COL)
+    opb.src = B;  // the gather addresses the whole input tensor
+  else
+    opb.src = (Cfg::LB == L_KC) ? B + (long long)bc.n0 * p.ldb : B + bc.n0;
+  opb.ld = p.ldb;
+  opb.rows_left = p.N - bc.n0;
+  opb.K = p.K;
+  opb.r0 = bc.n0;
+}
+
+// Per-column bias of the 4 columns a lane owns in the epilogue, fetched before the main loop so that
+// the latency disappears behind it.
+template <class Cfg>
+__device__ __forceinline__ void load_col_bias(const GemmParams& p, int n_wave0, int lane, float (&col_bias)[4]) {
+  using TO = typename Cfg::TO;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) col_bias[e] = 0.0f;
+  if (p.bias_axis == 1) {
+    const TO* bptr = reinterpret_cast<const TO*>(p.bias);
+    const int n = n_wave0 + (lane % (Cfg::WTN / 4)) * 4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (n + e < p.N) col_bias[e] = to_f32(bptr[n + e]);
+  }
+}
+
+// Step 5: fused epilogue + predicated store.  The MFMAs are issued with their operands swapped, so
+// an accumulator tile holds C transposed and each lane owns 4 consecutive columns of MI different
+// rows.  Storing that directly would scatter 8-byte pieces over as many cache lines, so each wave
+// transposes its accumulators through a private LDS region, MI rows at a time: written as they lie
+// in registers, read back so that consecutive lanes hold consecutive columns of one row, and stored
+// as whole 128-byte lines.  No workgroup barrier is involved: the region is private to the wave and
+// a wave's LDS operations complete in order (the fences are wave-scope, LDS-only).
+// Must be entered after a workgroup barrier that ends all use of the staging buffers.
+template <class Cfg, class Acc>
+__device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords& bc, int wave, int lane, int wm0, int wn0,
+                                         Acc (&acc)[Cfg::FM][Cfg::FN], const float (&col_bias)[4], unsigned char* smem) {
+  using TO = typename Cfg::TO;
+  constexpr int MI = Cfg::MI, FM = Cfg::FM, FN = Cfg::FN, WTN = Cfg::WTN;
+  TO* C = reinterpret_cast<TO*>(p.C) + (long long)bc.batch * p.strideC;
+  const TO* R = p.residual ? reinterpret_cast<const TO*>(p.residual) + (long long)bc.batch * p.strideR : nullptr;
+  const TO* bias = reinterpret_cast<const TO*>(p.bias);
+  constexpr int GROUPS = (MI == 32) ? 4 : 1;  // groups of 4 consecutive columns per accumulator tile
+  constexpr int ROW_BYTES = WTN * 4 + 16;     // +16: consecutive rows start 4 banks apart
+  constexpr int LANES_PER_ROW = WTN / 4;
+  constexpr int SLOTS = MI * LANES_PER_ROW;   // 16-byte pieces per pass
+  constexpr int READS = (SLOTS + 63) / 64;
+  static_assert(64 % LANES_PER_ROW == 0, "a lane must keep the same 4 columns in every read-back step");
+  unsigned char* region = smem + wave * (MI * ROW_BYTES);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int gq = 0; gq < GROUPS; ++gq) {
+        const int nl = j * MI + ((MI == 32) ? 8 * gq + 4 * (lane / 32) : 4 * (lane / 16));
+        const f32x4 v = {acc[i][j][4 * gq + 0], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+        *reinterpret_cast<f32x4*>(region + (lane % MI) * ROW_BYTES + nl * 4) = v;
+      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+#pragma unroll
+    for (int t = 0; t < READS; ++t) {
+      const int idx = t * 64 + lane;
+      const int row = idx / LANES_PER_ROW, c4 = idx % LANES_PER_ROW;
+      if (SLOTS % 64 == 0 || idx < SLOTS) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(region + row * ROW_BYTES + c4 * 16);
+        const float vv[4] = {v[0], v[1], v[2], v[3]};
+        store4<TO, Cfg::MAPPER>(p, C, R, bias, col_bias, bc.m0 + wm0 + i * MI + row, bc.n0 + wn0 + c4 * 4, vv);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The kernel, general schedule: two LDS stages, next tile staged through registers (the double
+// buffering of Section 3.1), fragments double-buffered in registers so that LDS reads of k step
+// ks+1 run under the MFMAs of k step ks.  Handles every load mode and every edge.
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   using T = typename Cfg::T;
-  using TO = typename Cfg::TO;
   using Acc = typename AccT<Cfg::MI>::type;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NT = Cfg::NT;
   constexpr int FM = Cfg::FM, FN = Cfg::FN, KS = Cfg::KS;
@@ -474,39 +657,12 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   const int lane = tid % 64;
   const int wave = tid / 64;
 
-  // ---- step 1: block-level task mapping ------------------------------------------------------
-  // Workgroups are handed to the 8 accelerator dies (XCDs) round-robin; renumber them so that each
-  // die, which has a private L2, works on one contiguous run of tiles of the grouped traversal.
-  const int total = p.total_blocks;
-  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-  const int per = total / 8, extra = total % 8;
-  const int logical = xcd * per + (xcd < extra ? xcd : extra) + slot;
-  const int tiles = p.tiles_m * p.tiles_n;
-  const int batch = logical / tiles;
-  const tmap::Task tile = tmap::GroupedSpatial{p.tiles_m, p.tiles_n, p.group}.task(logical - batch * tiles);
-  const int m0 = tile.i * BM, n0 = tile.j * BN;
-
+  const BlockCoords bc = block_coords<BM, BN>(p);  // step 1
   OpA opa;
   OpB opb;
-  {
-    const T* A = reinterpret_cast<const T*>(p.A) + (long long)batch * p.strideA;
-    const T* B = reinterpret_cast<const T*>(p.B) + (long long)batch * p.strideB;
-    opa.src = (Cfg::LA == L_KC) ? A + (long long)m0 * p.lda : A + m0;
-    opa.ld = p.lda;
-    opa.rows_left = p.M - m0;
-    opa.K = p.K;
-    opa.r0 = m0;
-    if constexpr (Cfg::MODE_B == LD_IM2COL)
-      opb.src = B;  // the gather addresses the whole input tensor
-    else
-      opb.src = (Cfg::LB == L_KC) ? B + (long long)n0 * p.ldb : B + n0;
-    opb.ld = p.ldb;
-    opb.rows_left = p.N - n0;
-    opb.K = p.K;
-    opb.r0 = n0;
-  }
+  setup_operands<Cfg>(p, bc, opa, opb);
 
-  // ---- step 4 (set-up): wave-level task mapping spatial(WAVES_M, WAVES_N) o repeat(FM, FN) ------
+  // step 4 (set-up): wave-level task mapping spatial(WAVES_M, WAVES_N) o repeat(FM, FN)
   const tmap::Task wt = tmap::Spatial<Cfg::WAVES_M, Cfg::WAVES_N>::task(wave, 0);
   const int wm0 = wt.i * Cfg::WTM, wn0 = wt.j * Cfg::WTN;
 
@@ -518,66 +674,249 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
 #pragma unroll
       for (int r = 0; r < (int)(sizeof(Acc) / 4); ++r) acc[i][j][r] = 0.0f;
 
-  const int KT = (p.K + BK - 1) / BK;
-  u32x4 ra[OpA::NL], rb[OpB::NL];
+  float col_bias[4];
+  load_col_bias<Cfg>(p, bc.n0 + wn0, lane, col_bias);
 
   // ---- steps 2 + 3: double-buffered main loop --------------------------------------------------
-  if (KT > 0) {
-    opa.load(ra, tid, 0, p.g);
-    opb.load(rb, tid, 0, p.g);
-    opa.store(ra, tid, smem);
-    opb.store(rb, tid, smem + Cfg::A_BYTES);
-    __syncthreads();
-  }
-  for (int kt = 0; kt < KT; ++kt) {
+  const int KT = (p.K + BK - 1) / BK;
+  const int KT_full = p.K / BK;  // tiles that lie entirely inside K
+  u32x4 ra[OpA::NL], rb[OpB::NL];
+  opa.init(tid);
+  opb.init(tid);
+
+  auto fetch = [&](int kt) {  // global -> registers
+    if (kt < KT_full) {
+      opa.load_full(ra, tid, kt * BK, p.g);
+      opb.load_full(rb, tid, kt * BK, p.g);
+    } else {
+      opa.load_edge(ra, tid, kt * BK, p.g);
+      opb.load_edge(rb, tid, kt * BK, p.g);
+    }
+  };
+  auto commit = [&](unsigned char* stage) {  // registers -> LDS
+    opa.store(ra, tid, stage);
+    opb.store(rb, tid, stage + Cfg::A_BYTES);
+  };
+  typename OpA::Frag fa[2][FM];
+  typename OpB::Frag fb[2][FN];
+  auto load_frags = [&](int buf, const unsigned char* stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa[buf][i] = opa.fragment(stage, lane, wm0, i, ks);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) fb[buf][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, ks);
+  };
+  auto mfmas = [&](int buf) {
+    // operands swapped on purpose: the accumulator tile then holds C transposed (see epilogue)
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) acc[i][j] = mfma_op(fb[buf][j], fa[buf][i], acc[i][j]);
+  };
+
+  // One iteration of the K loop.  `next`: 1 = tile kt+1 lies entirely inside K (predicate-free loads),
+  // 2 = it is the last, partial tile, 0 = there is none.
+  //   top        global loads of tile kt+1 -> registers
+  //   ks < KS-1  LDS reads of k step ks+1, MFMAs of k step ks; during k step KS-2 the registers of
+  //              tile kt+1 are written to the other LDS buffer
+  //   barrier    every wave has written its share of tile kt+1 and has read all of tile kt
+  //   ks = KS-1  LDS reads of k step 0 of tile kt+1, MFMAs of the last k step of tile kt
+  // On entry frag[0] holds k step 0 of tile kt.  (With an odd number of k steps the fragment
+  // buffers cannot alternate across tiles; that case runs the plain load-then-multiply order.)
+  auto iteration = [&](int kt, auto next) {
     unsigned char* cur = smem + (kt & 1) * Cfg::STAGE_BYTES;
     unsigned char* nxt = smem + ((kt + 1) & 1) * Cfg::STAGE_BYTES;
-    const bool more = kt + 1 < KT;
-    if (more) {  // next tile: global -> registers, in flight during the MFMAs below
-      opa.load(ra, tid, (kt + 1) * BK, p.g);
-      opb.load(rb, tid, (kt + 1) * BK, p.g);
+    if constexpr (next.value == 1) {
+      opa.load_full(ra, tid, (kt + 1) * BK, p.g);
+      opb.load_full(rb, tid, (kt + 1) * BK, p.g);
+    } else if constexpr (next.value == 2) {
+      opa.load_edge(ra, tid, (kt + 1) * BK, p.g);
+      opb.load_edge(rb, tid, (kt + 1) * BK, p.g);
     }
-    const unsigned char* ta = cur;
-    const unsigned char* tb = cur + Cfg::A_BYTES;
+    // keep the global loads where they are written: issued before the MFMAs, so that their latency
+    // overlaps the contraction instead of being paid right before the LDS stores
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (KS % 2 == 0) {
+#pragma unroll
+      for (int ks = 0; ks + 1 < KS; ++ks) {
+        load_frags((ks + 1) & 1, cur, ks + 1);
+        if constexpr (next.value != 0) {
+          if (ks == KS - 2) commit(nxt);
+        }
+        mfmas(ks & 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (next.value != 0) {
+        __syncthreads();
+        load_frags(0, nxt, 0);
+      }
+      mfmas((KS - 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        load_frags(0, cur, ks);
+        mfmas(0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (next.value != 0) {
+        commit(nxt);
+        __syncthreads();
+      }
+    }
+  };
+
+  if (KT > 0) {
+    fetch(0);
+    commit(smem);
+    __syncthreads();
+    if constexpr (KS % 2 == 0) load_frags(0, smem, 0);
+    int kt = 0;
+    for (; kt + 1 < KT_full; ++kt) iteration(kt, std::integral_constant<int, 1>{});
+    if (kt + 1 < KT) {
+      iteration(kt, std::integral_constant<int, 2>{});
+      ++kt;
+    }
+    iteration(kt, std::integral_constant<int, 0>{});
+    __syncthreads();  // the epilogue reuses the LDS
+  }
+
+  epilogue<Cfg>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The kernel, large-tile schedule: 8 waves (2 per SIMD), vector mode only.
+//
+// K is consumed in stages of BK; LDS holds a ring of 4 stages.  Stage s+3 is requested with direct
+// global -> LDS loads while stage s is being multiplied, so a load has two full stages to land.
+// The two waves of a SIMD run half a stage apart: in every phase one of them issues nothing but
+// MFMAs (at raised priority) while the other issues the LDS reads of its next fragments and the
+// global loads -- the LDS pipe and the matrix cores are busy at the same time instead of taking
+// turns.  Phases are separated by bare s_barrier instructions; what must be complete before a
+// barrier is waited for explicitly:
+//   * the wave's own LDS reads of stage s (its buffer is overwritten by loads issued right after
+//     the barrier by the other wave group),
+//   * the wave's own direct loads of stage s+1 (read by the other wave group right after).
+// The second wave group enters the loop one barrier late and leaves it one barrier early.
+// A last partial stage (K not a multiple of BK) is staged through registers with zero fill after the
+// ring has drained.
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams p) {
+  using T = typename Cfg::T;
+  using Acc = typename AccT<Cfg::MI>::type;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NT = Cfg::NT;
+  constexpr int FM = Cfg::FM, FN = Cfg::FN, KS = Cfg::KS;
+  static_assert(Cfg::NWAVES == 8 && !Cfg::IS_F32 && Cfg::MODE_A == LD_VEC && Cfg::MODE_B == LD_VEC && Cfg::STAGES == 4,
+                "ping-pong schedule: 8 waves, 16-bit vector mode, 4 LDS stages");
+  using OpA = Operand<T, BM, BK, Cfg::LA, LD_VEC, NT, MI>;
+  using OpB = Operand<T, BN, BK, Cfg::LB, LD_VEC, NT, MI>;
+  constexpr int LOADS = OpA::NL + OpB::NL;  // direct loads per thread per stage
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem[Cfg::LDS_BYTES];
+
+  const int tid = threadIdx.x;
+  const int lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int grp = wave / 4;  // waves w and w+4 share a SIMD
+
+  const BlockCoords bc = block_coords<BM, BN>(p);
+  OpA opa;
+  OpB opb;
+  setup_operands<Cfg>(p, bc, opa, opb);
+  const tmap::Task wt = tmap::Spatial<Cfg::WAVES_M, Cfg::WAVES_N>::task(wave, 0);
+  const int wm0 = wt.i * Cfg::WTM, wn0 = wt.j * Cfg::WTN;
+
+  Acc acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < (int)(sizeof(Acc) / 4); ++r) acc[i][j][r] = 0.0f;
+
+  float col_bias[4];
+  load_col_bias<Cfg>(p, bc.n0 + wn0, lane, col_bias);
+  __builtin_amdgcn_s_waitcnt(0);  // nothing outstanding before the hand-counted loads begin
+
+  typename OpA::Frag fa[KS][FM];
+  typename OpB::Frag fb[KS][FN];
+  auto load_frags = [&](const unsigned char* stage) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      typename OpA::Frag fa[FM];
-      typename OpB::Frag fb[FN];
 #pragma unroll
-      for (int i = 0; i < FM; ++i) fa[i] = opa.fragment(ta, lane, wm0, i, ks);
+      for (int i = 0; i < FM; ++i) fa[ks][i] = opa.fragment(stage, lane, wm0, i, ks);
 #pragma unroll
-      for (int j = 0; j < FN; ++j) fb[j] = opb.fragment(tb, lane, wn0, j, ks);
-      // operands swapped on purpose: the accumulator tile then holds C transposed, so that each
-      // lane owns 4 consecutive columns of one row of C and can store them with one access
+      for (int j = 0; j < FN; ++j) fb[ks][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, ks);
+    }
+  };
+  auto mfmas = [&]() {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_op(fb[j], fa[i], acc[i][j]);
-    }
-    if (more) {  // registers -> the other LDS buffer
-      opa.store(ra, tid, nxt);
-      opb.store(rb, tid, nxt + Cfg::A_BYTES);
-    }
-    __syncthreads();
-  }
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_op(fb[ks][j], fa[ks][i], acc[i][j]);
+  };
+  auto phase_barrier = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;
+  auto request = [&](int s) {  // direct loads of stage s into ring slot s % 4
+    const unsigned slot = smem_lds + (unsigned)((s & 3) * Cfg::STAGE_BYTES);
+    opa.load_direct(slot, wave, s * BK);
+    opb.load_direct(slot + Cfg::A_BYTES, wave, s * BK);
+  };
+  // wait until at most `younger` stages of this wave's direct loads are still in flight, and all LDS reads are back
+  auto wait_stage = [&](int younger) {
+    if (younger >= 2)
+      __builtin_amdgcn_s_waitcnt(0x0070 | ((2 * LOADS) & 15) | (((2 * LOADS) >> 4) << 14));
+    else if (younger == 1)
+      __builtin_amdgcn_s_waitcnt(0x0070 | (LOADS & 15) | ((LOADS >> 4) << 14));
+    else
+      __builtin_amdgcn_s_waitcnt(0x0070);
+  };
 
-  // ---- step 5: fused epilogue + predicated store -----------------------------------------------
-  TO* C = reinterpret_cast<TO*>(p.C) + (long long)batch * p.strideC;
-  const TO* R = p.residual ? reinterpret_cast<const TO*>(p.residual) + (long long)batch * p.strideR : nullptr;
-  const TO* bias = reinterpret_cast<const TO*>(p.bias);
-  constexpr int GROUPS = (MI == 32) ? 4 : 1;  // groups of 4 consecutive columns per accumulator tile
-#pragma unroll
-  for (int j = 0; j < FN; ++j)
-#pragma unroll
-    for (int gq = 0; gq < GROUPS; ++gq) {
-      const int n = n0 + wn0 + j * MI + ((MI == 32) ? 8 * gq + 4 * (lane / 32) : 4 * (lane / 16));
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int m = m0 + wm0 + i * MI + lane % MI;
-        const float v[4] = {acc[i][j][4 * gq + 0], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
-        store4<TO, Cfg::MAPPER>(p, C, R, bias, m, n, v);
-      }
+  const int S = p.K / BK;  // full stages
+  if (S > 0) {
+    opa.init_direct(tid);
+    opb.init_direct(tid);
+    const int pre = S < 3 ? S : 3;
+    for (int s = 0; s < pre; ++s) request(s);
+    wait_stage(pre - 1);
+    phase_barrier();
+    if (grp == 1) phase_barrier();
+    for (int s = 0; s < S; ++s) {
+      // ---- memory phase
+      load_frags(smem + (s & 3) * Cfg::STAGE_BYTES);
+      if (s + 3 < S) request(s + 3);
+      wait_stage((s + 2 < S) + (s + 3 < S));
+      phase_barrier();
+      // ---- compute phase
+      __builtin_amdgcn_s_setprio(1);
+      mfmas();
+      __builtin_amdgcn_s_setprio(0);
+      phase_barrier();
     }
+    if (grp == 0) phase_barrier();
+  }
+  if (S * BK < p.K) {  // the partial last stage, through registers with zero fill
+    u32x4 ra[OpA::NL], rb[OpB::NL];
+    opa.init(tid);
+    opb.init(tid);
+    opa.load_edge(ra, tid, S * BK, p.g);
+    opb.load_edge(rb, tid, S * BK, p.g);
+    __syncthreads();
+    opa.store(ra, tid, smem);
+    opb.store(rb, tid, smem + Cfg::A_BYTES);
+    __syncthreads();
+    load_frags(smem);
+    mfmas();
+  }
+  __syncthreads();  // the epilogue reuses the LDS
+
+  epilogue<Cfg>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
 }
 
 }  // namespace hidet

@@ -12,9 +12,9 @@
 #if HIDET_TYPE == 0
 using ElemT = float;
 #define X16(...)
-#define X32(idx, BM, BN, BK, WM, WN, MI, TA)                                              \
+#define X32(idx, BM, BN, BK, WM, WN, MI, TA, SC)                                              \
   extern "C" void HIDET_CAT(hidet_register_, idx, _, HIDET_TYPE)(hidet::Registry * r) {   \
-    hidet::register_config<ElemT, BM, BN, BK, WM, WN, MI, TA>(*r, idx, HIDET_TYPE);       \
+    hidet::register_config<ElemT, BM, BN, BK, WM, WN, MI, TA, SC>(*r, idx, HIDET_TYPE);       \
   }
 #else
 #if HIDET_TYPE == 1
@@ -23,9 +23,9 @@ using ElemT = hidet::f16;
 using ElemT = hidet::bf16;
 #endif
 #define X32(...)
-#define X16(idx, BM, BN, BK, WM, WN, MI, TA)                                              \
+#define X16(idx, BM, BN, BK, WM, WN, MI, TA, SC)                                              \
   extern "C" void HIDET_CAT(hidet_register_, idx, _, HIDET_TYPE)(hidet::Registry * r) {   \
-    hidet::register_config<ElemT, BM, BN, BK, WM, WN, MI, TA>(*r, idx, HIDET_TYPE);       \
+    hidet::register_config<ElemT, BM, BN, BK, WM, WN, MI, TA, SC>(*r, idx, HIDET_TYPE);       \
   }
 #endif
 

@@ -14,7 +14,7 @@ constexpr int kNumTypes = 3;     // index = hidet_dtype_t of the inputs: 0 f32, 
 constexpr int kNumVariants = 10; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode
 
 struct ConfigRow {
-  int index, bm, bn, bk, waves_m, waves_n, mfma, trans_a, is_f32;
+  int index, bm, bn, bk, waves_m, waves_n, mfma, trans_a, sched, is_f32;
 };
 
 struct Registry {
@@ -26,23 +26,26 @@ inline int conv_variant(int elem_mode) { return 8 + (elem_mode ? 1 : 0); }
 
 template <class Cfg>
 hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
-  hipLaunchKernelGGL(gemm_kernel<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
+  if constexpr (Cfg::SCHED == SCHED_PINGPONG)
+    hipLaunchKernelGGL(gemm_kernel_pingpong<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
+  else
+    hipLaunchKernelGGL(gemm_kernel<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
   return hipGetLastError();
 }
 
 // Fills the launchers of one (configuration, input type) pair.
-template <typename T, int BM, int BN, int BK, int WM, int WN, int MI, int TRANS_A>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int MI, int TRANS_A, int SCHED>
 void register_config(Registry& r, int index, int type_index) {
   LaunchFn* v = r.fn[index][type_index];
   // row-major A: KC;  row-major B: MC;  transposed B: KC;  transposed A: MC
-  v[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+  v[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
   v[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
-  v[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+  v[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
   v[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
   if constexpr (TRANS_A != 0) {
-    v[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+    v[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
     v[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
-    v[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+    v[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
     v[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
   }
   // convolution: weights are a row-major OC x (IC*KH*KW) matrix, B is the img2col gather, C is NCHW
