@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--k", type=int, default=4096)
     ap.add_argument("--config", type=int, default=None, help="force a tile configuration instead of tuning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run 10 plain device-to-device copies of MIB mebibytes "
+                         "(known traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by output tiles without any exchange; "
@@ -48,6 +51,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     hb.lib()  # raises if the HIP extension has not been built
+
+    if args.copy_calibration > 0:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 10}))
+        return
 
     dt = args.dtype
     tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[dt]

@@ -80,12 +80,20 @@ struct GemmParams {
 //   column of consecutive rows, so consecutive rows must land in different bank groups.
 //   MC tiles are read with the transposing 8-byte read: a group of 16 lanes reads 4 consecutive
 //   k rows x 32 bytes, so those 4 rows must land in different bank groups.
+// Any per-row permutation is correct (loads and fragment reads apply the same one); these were
+// chosen with an LDS micro-benchmark so that the fragment reads run at the LDS peak
+// (256 B/clk for 16-byte reads, about 160 B/clk for the transposing read).
 // ---------------------------------------------------------------------------------------------
 template <int CPR>
 __device__ __forceinline__ constexpr int swz_kc(int row) {
-  if constexpr (CPR >= 16) return row & 15;
-  if constexpr (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
-  if constexpr (CPR == 4) return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+  // A 16-byte LDS read is served in four steps of 16 lanes: lanes 8i..8i+7 together with lanes
+  // 32+8i..32+8i+7 (measured).  In the fragment reads those 16 lanes are 8 consecutive rows times
+  // a pair of chunks that differ in bit 0 (32x32 MFMA: k groups 0,1) or in bit 1 (16x16 MFMA: k
+  // groups 0,2 / 1,3).  Rows that start at the same bank must therefore get swizzles whose XOR
+  // separates both kinds of pair.
+  if constexpr (CPR >= 16) return ((row & 1) * 3) | ((row & 6) << 1);
+  if constexpr (CPR == 8) return (((row >> 1) & 1) * 3) | (((row >> 2) & 1) << 2);
+  if constexpr (CPR == 4) return ((row >> 2) & 1) * 3;
   return 0;
 }
 template <int CPR, int MI>
