@@ -21,8 +21,85 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}  # 256 CUs x 4 SIMDs x FLOP/clk x 2.4 GHz (dense MFMA)
 
 # HBM bytes per launch of the dominant kernel at 4096^3, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
-# (profiles/gemm_f16_4096_pmc.txt); None until measured for the workload at hand.
-MEASURED_TRAFFIC_BYTES = {}
+# scaled by a plain copy of known size (profiles/gemm_pingpong_f16_4096.md); None for workloads not measured.
+MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235323351}
+
+
+def side_report(torch, hb, wl, steps=200):
+    """Time the other workloads with the tuner (every configuration of the space, `steps` launches each, winner reported):
+    list of dicts with us, TFLOP/s, % of peak MFMA and algorithmic GB/s."""
+    import numpy as np
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}
+
+    def dev(stored, dt):
+        if stored is None:
+            return None
+        if dt == "bf16":
+            return torch.from_numpy(np.ascontiguousarray(stored).view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+
+    def timed(fn, tune):
+        # timed inside the library (a tight C++ launch loop between two HIP events): a Python call per
+        # launch costs more than these small kernels run
+        t0 = time.perf_counter()
+        cfg, us = tune()
+        tune_s = time.perf_counter() - t0
+        return us, cfg, tune_s
+
+    rows = []
+
+    def add(name, dt, flops, nbytes, us, cfg, tune_s):
+        info = hb.hidet_config_info(cfg)
+        rows.append({"workload": name, "dtype": dt, "us": round(us, 2), "TFLOPs": round(flops / us * 1e-6, 2),
+                     "pct_peak_mfma": round(100 * flops / us * 1e-6 / PEAK_TFLOPS[dt], 2),
+                     "algorithmic_GBps": round(nbytes / us * 1e-3, 1), "pct_of_8TBps": round(100 * nbytes / us * 1e-3 / 8000, 2),
+                     "tile_config": cfg, "tile": "%dx%dx%d/%dx%d/mfma%d" % (info["block_m"], info["block_n"], info["block_k"],
+                                                                            info["waves_m"], info["waves_n"], info["mfma"]),
+                     "tuning_seconds": round(tune_s, 3)})
+
+    def gemm_row(c):
+        dt = c["dtype"]
+        es = 4 if dt == "f32" else 2
+        A, B = dev(c["A"], dt), dev(c["B"], dt)
+        bias, res = dev(c["bias"], dt), dev(c["residual"], dt)
+        C = torch.empty((c["M"], c["N"]), dtype=tdt[dt], device="cuda")
+        axis = {None: hb.HIDET_BIAS_NONE, "col": hb.HIDET_BIAS_PER_COL, "row": hb.HIDET_BIAS_PER_ROW}[c["bias_axis"]]
+        epi = hb.make_epilogue(alpha=c.get("alpha", 1.0), bias=bias, bias_axis=axis, residual=res, relu=c.get("relu", False))
+        us, cfg, ts = timed(lambda cfg: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg),
+                            lambda: hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=steps))
+        nbytes = (c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] * (2 if res is not None else 1)) * es
+        add(c["name"], dt, 2.0 * c["M"] * c["N"] * c["K"], nbytes, us, cfg, ts)
+
+    for c in wl.config1():
+        gemm_row(c)
+    for dt in ("f16", "bf16"):
+        for c in wl.config2(dt):
+            gemm_row(c)
+    for c in wl.config3("f16"):
+        x, w, b = dev(c["x"], "f16"), dev(c["w"], "f16"), dev(c["bias"], "f16")
+        y = torch.empty((c["Nb"], c["OC"], c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+        sp = dict(stride=(c["stride"], c["stride"]), pad=(c["pad"], c["pad"]))
+        us, cfg, ts = timed(lambda cfg: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, config=cfg, **sp),
+                            lambda: hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp))
+        flops = 2.0 * c["Nb"] * c["OC"] * c["OH"] * c["OW"] * c["IC"] * c["KH"] * c["KW"]
+        add(c["name"], "f16", flops, (x.numel() + w.numel() + y.numel()) * 2, us, cfg, ts)
+    for c in wl.config4("f16"):
+        Q, Kt, V, S = (dev(c[k], "f16") for k in ("Q", "K", "V", "S"))
+        b, s, d = c["batch"], c["seq"], c["d"]
+        scores = torch.empty((b, s, s), dtype=torch.float16, device="cuda")
+        ctx = torch.empty((b, s, d), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(alpha=c["alpha"])
+        us, cfg, ts = timed(lambda cfg: hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi, config=cfg),
+                            lambda: hb.hidet_tune_gemm(Q, Kt, scores, transB=True, epilogue=epi, iters=steps))
+        add(c["name"] + "_QKt", "f16", 2.0 * b * s * s * d, (2 * b * s * d + b * s * s) * 2, us, cfg, ts)
+        us, cfg, ts = timed(lambda cfg: hb.hidet_batched_gemm(S, V, ctx, config=cfg),
+                            lambda: hb.hidet_tune_gemm(S, V, ctx, iters=steps))
+        add(c["name"] + "_SV", "f16", 2.0 * b * s * s * d, (2 * b * s * d + b * s * s) * 2, us, cfg, ts)
+    for dt in ("f16", "bf16"):
+        for K in (4096, 1024):
+            gemm_row(wl.config5(dt, K=K))
+    return rows
 
 
 def main():
@@ -34,6 +111,9 @@ def main():
     ap.add_argument("--k", type=int, default=4096)
     ap.add_argument("--config", type=int, default=None, help="force a tile configuration instead of tuning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", default=None, metavar="PATH",
+                    help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
+                         "and write the table to PATH as JSON; the headline line is printed as usual")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 10 plain device-to-device copies of MIB mebibytes "
                          "(known traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters)")
@@ -99,6 +179,8 @@ def main():
     flops = 2.0 * M * N * K
     tflops = flops / (ms_per_step * 1e-3) / 1e12
 
+    # what the matrix cores alone sustain on these operand values (clock is power-limited and data-dependent)
+    ceil_tflops, ceil_mhz = hb.hidet_probe_mfma_peak(A, mfma=cfg_info["mfma"])
     algo_bytes = (M * K + K * N + M * N + N) * 2  # every operand and the output once
     out = {
         "metric": "fused GEMM/implicit-GEMM conv TFLOP/s and % of MI355X peak MFMA, 1 GPU",
@@ -121,6 +203,9 @@ def main():
             "tuning_seconds": round(tune_s, 3),
             "pct_of_peak_mfma": round(100.0 * tflops / PEAK_TFLOPS[dt], 2),
             "algorithmic_hbm_GBps": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+            "mfma_only_ceiling_TFLOPs_same_data": round(ceil_tflops, 1),
+            "mfma_only_ceiling_sclk_MHz": round(ceil_mhz),
+            "pct_of_mfma_only_ceiling": round(100.0 * tflops / ceil_tflops, 2) if ceil_tflops > 0 else None,
         },
         "roofline": {
             "bound": "mfma",
@@ -131,6 +216,11 @@ def main():
             "traffic": MEASURED_TRAFFIC_BYTES.get((dt, M, N, K)),
         },
     }
+
+    if args.report:
+        out_report = side_report(torch, hb, wl)
+        with open(args.report, "w") as fh:
+            json.dump(out_report, fh, indent=1)
 
     if not args.no_cpu_baseline:
         import oracle

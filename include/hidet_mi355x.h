@@ -177,6 +177,19 @@ hidet_status_t hidet_taskmap_tasks(int32_t index, int32_t worker, int32_t* tasks
 hidet_status_t hidet_block_task(int32_t tiles_m, int32_t tiles_n, int32_t group, int32_t w, int32_t* tile_i,
                                 int32_t* tile_j);
 
+/*
+ * Matrix-core ceiling probe (measurement aid, Section 6 style reporting): every wavefront of the GPU
+ * issues independent MFMAs of shape `mfma` (16 or 32) back to back on operands read from `sample`
+ * (device pointer, >= 4096 bytes of dtype `dtype`; the sustained clock under dense MFMA load depends
+ * on the operand values, so pass a piece of the real input).  Reports the sustained TFLOP/s and the
+ * average shader clock.  `scratch` is a device buffer of at least hidet_probe_scratch_bytes() bytes,
+ * 8-byte aligned, whose contents are overwritten.  Synchronises `stream`.
+ */
+hidet_status_t hidet_probe_mfma_peak(int32_t dtype, int32_t mfma, const void* sample, int64_t sample_bytes,
+                                     void* scratch, int64_t scratch_bytes, void* stream, float* tflops,
+                                     float* sclk_mhz);
+int64_t hidet_probe_scratch_bytes(void);
+
 const char* hidet_status_string(int32_t status);
 /* Library version string and the GPU architecture the kernels were compiled for ("gfx950"). */
 const char* hidet_version(void);

@@ -51,6 +51,7 @@ EXPORTS = (
     "hidet_conv2d_implicit_gemm_cfg", "hidet_config_count", "hidet_config_info", "hidet_tune_gemm", "hidet_tune_conv2d",
     "hidet_tune_last_times", "hidet_tune_clear", "hidet_tune_save", "hidet_tune_load", "hidet_taskmap_count",
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
+    "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes",
 )
 
 _lib = None
@@ -85,6 +86,9 @@ def lib():
         L.hidet_taskmap_info.argtypes = [_i32, ctypes.c_char_p, _i32] + [ctypes.POINTER(_i32)] * 4
         L.hidet_taskmap_tasks.argtypes = [_i32, _i32, ctypes.POINTER(_i32), _i32]
         L.hidet_block_task.argtypes = [_i32] * 4 + [ctypes.POINTER(_i32)] * 2
+        L.hidet_probe_mfma_peak.argtypes = [_i32, _i32, _vp, _i64, _vp, _i64, _vp, ctypes.POINTER(ctypes.c_float),
+                                            ctypes.POINTER(ctypes.c_float)]
+        L.hidet_probe_scratch_bytes.restype = _i64
         L.hidet_status_string.argtypes = [_i32]
         L.hidet_status_string.restype = ctypes.c_char_p
         L.hidet_version.restype = ctypes.c_char_p
@@ -275,6 +279,18 @@ def hidet_block_task(tiles_m, tiles_n, group, w):
     i, j = _i32(), _i32()
     _check(lib().hidet_block_task(tiles_m, tiles_n, group, w, ctypes.byref(i), ctypes.byref(j)), "hidet_block_task")
     return i.value, j.value
+
+
+def hidet_probe_mfma_peak(sample, mfma=16, stream=None):
+    """MFMA-only ceiling on operands taken from `sample` (a GPU tensor of the input dtype); returns (TFLOP/s, sclk MHz)."""
+    n = lib().hidet_probe_scratch_bytes()
+    scratch = torch.empty(n, dtype=torch.uint8, device=sample.device)
+    tf, mhz = ctypes.c_float(0.0), ctypes.c_float(0.0)
+    flat = sample.reshape(-1)
+    st = lib().hidet_probe_mfma_peak(_dtype(sample), mfma, _ptr(flat), flat.numel() * flat.element_size(), _ptr(scratch), n,
+                                     _stream(stream), ctypes.byref(tf), ctypes.byref(mhz))
+    _check(st, "hidet_probe_mfma_peak")
+    return tf.value, mhz.value
 
 
 def hidet_version():

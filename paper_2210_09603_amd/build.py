@@ -74,10 +74,11 @@ def build(force=False, jobs=None, verbose=True):
             objs.append(obj)
             if not os.path.exists(obj):
                 tasks.append((os.path.join(CSRC, "instances.hip"), obj, ["-DHIDET_TU=%d" % idx, "-DHIDET_TYPE=%d" % t]))
-    api = os.path.join(BUILD, "api.o")
-    objs.append(api)
-    if not os.path.exists(api):
-        tasks.append((os.path.join(CSRC, "api.hip"), api, []))
+    for name in ("api", "probe"):
+        obj = os.path.join(BUILD, name + ".o")
+        objs.append(obj)
+        if not os.path.exists(obj):
+            tasks.append((os.path.join(CSRC, name + ".hip"), obj, []))
     jobs = jobs or min(8, os.cpu_count() or 1)
     failed = False
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:

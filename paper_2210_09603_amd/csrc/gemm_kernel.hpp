@@ -84,16 +84,22 @@ struct GemmParams {
 // chosen with an LDS micro-benchmark so that the fragment reads run at the LDS peak
 // (256 B/clk for 16-byte reads, about 160 B/clk for the transposing read).
 // ---------------------------------------------------------------------------------------------
-template <int CPR>
+template <int CPR, int MI>
 __device__ __forceinline__ constexpr int swz_kc(int row) {
-  // A 16-byte LDS read is served in four steps of 16 lanes: lanes 8i..8i+7 together with lanes
-  // 32+8i..32+8i+7 (measured).  In the fragment reads those 16 lanes are 8 consecutive rows times
-  // a pair of chunks that differ in bit 0 (32x32 MFMA: k groups 0,1) or in bit 1 (16x16 MFMA: k
-  // groups 0,2 / 1,3).  Rows that start at the same bank must therefore get swizzles whose XOR
-  // separates both kinds of pair.
-  if constexpr (CPR >= 16) return ((row & 1) * 3) | ((row & 6) << 1);
-  if constexpr (CPR == 8) return (((row >> 1) & 1) * 3) | (((row >> 2) & 1) << 2);
-  if constexpr (CPR == 4) return ((row >> 2) & 1) * 3;
+  // Chosen per MFMA shape from measurements (LDS micro-benchmark and the SQ_LDS_BANK_CONFLICT counter
+  // of the running kernel): in the 32x32 fragment read the 32 lanes of a half-wave are 32 consecutive
+  // rows of one chunk column; in the 16x16 read they are 16 consecutive rows times two adjacent chunk
+  // columns.  Rows that start at the same bank must spread over all chunk positions in the first case
+  // and must keep the two columns apart in the second.
+  if constexpr (MI == 32) {
+    if constexpr (CPR >= 16) return row & 15;
+    if constexpr (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
+    if constexpr (CPR == 4) return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+  } else {
+    if constexpr (CPR >= 16) return ((row & 1) * 3) | ((row & 6) << 1);
+    if constexpr (CPR == 8) return (((row >> 1) & 1) * 3) | (((row >> 2) & 1) << 2);
+    if constexpr (CPR == 4) return ((row >> 2) & 1) * 3;
+  }
   return 0;
 }
 template <int CPR, int MI>
@@ -346,7 +352,7 @@ struct Operand {
     for (int q = 0; q < NL; ++q) {
       const int pos = q * NT + tid;
       const int row = pos / CPR, pc = pos % CPR;
-      const int lc = pc ^ ((LAYOUT == L_KC) ? swz_kc<CPR>(row) : swz_mc<CPR, MI>(row));
+      const int lc = pc ^ ((LAYOUT == L_KC) ? swz_kc<CPR, MI>(row) : swz_mc<CPR, MI>(row));
       if constexpr (LAYOUT == L_KC) {
         const int r = row < rows_left ? row : rows_left - 1;
         doff[q] = r * (int)ld + lc * VEC;
@@ -402,7 +408,7 @@ struct Operand {
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
       if constexpr (!IS_F32) {
-        const int swz = (LAYOUT == L_KC) ? swz_kc<CPR>(t.i) : swz_mc<CPR, MI>(t.i);
+        const int swz = (LAYOUT == L_KC) ? swz_kc<CPR, MI>(t.i) : swz_mc<CPR, MI>(t.i);
         *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = regs[q];
       } else if constexpr (LAYOUT == L_MC) {
         *reinterpret_cast<u32x4*>(tile + (t.i * CPR + t.j) * 16) = regs[q];
@@ -425,7 +431,7 @@ struct Operand {
     } else if constexpr (LAYOUT == L_KC) {
       const int r = w0 + f * MI + lane % MI;
       const int c = ks * KGROUPS + lane / MI;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(tile + (r * CPR + (c ^ swz_kc<CPR>(r))) * 16);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(tile + (r * CPR + (c ^ swz_kc<CPR, MI>(r))) * 16);
       return __builtin_bit_cast(Frag, v);
     } else {
       // transposing read: within each group of 16 lanes, lane s supplies the address of 4
@@ -516,10 +522,12 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
 #pragma unroll
   for (int e = 0; e < 4; ++e) o[e] = from_f32<TO>(v[e]);
   if (whole) {
+    // streaming stores: the output is not read again by this kernel, and lines that do not linger
+    // dirty in L2 shorten the write-back at the end of the kernel
     if constexpr (sizeof(TO) == 2)
-      *reinterpret_cast<u32x2*>(C + off) = *reinterpret_cast<const u32x2*>(o);
+      __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(o), reinterpret_cast<u32x2*>(C + off));
     else
-      *reinterpret_cast<u32x4*>(C + off) = *reinterpret_cast<const u32x4*>(o);
+      __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(o), reinterpret_cast<u32x4*>(C + off));
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {

@@ -250,3 +250,14 @@ def test_tuner_enumerates_the_space_and_caches(tmp_path):
     hb.hidet_gemm(A, B, C, epilogue=epi)
     torch.cuda.synchronize()
     assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ measurement aid
+def test_mfma_ceiling_probe_reports_plausible_numbers():
+    sample = torch.rand(1 << 16, device="cuda").to(torch.float16) * 2 - 1
+    for mfma in (16, 32):
+        tflops, mhz = hb.hidet_probe_mfma_peak(sample, mfma=mfma)
+        _say("mfma %d ceiling: %.0f TFLOP/s at %.0f MHz" % (mfma, tflops, mhz))
+        assert 200.0 < tflops < 2600.0 and 500.0 < mhz < 2600.0
+    t32, _ = hb.hidet_probe_mfma_peak(torch.rand(1 << 14, device="cuda"), mfma=32)
+    assert 20.0 < t32 < 160.0

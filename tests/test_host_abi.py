@@ -118,6 +118,18 @@ def test_batched_and_conv_argument_validation():
     assert hb.lib().hidet_status_string(3) == b"misaligned pointer"
 
 
+def test_probe_argument_validation():
+    L = hb.lib()
+    n = L.hidet_probe_scratch_bytes()
+    assert n >= 256 * 512 * 4
+    f = ctypes.c_float()
+    assert L.hidet_probe_mfma_peak(hb.HIDET_F16, 16, None, 8192, 0x1000, n, None, ctypes.byref(f), ctypes.byref(f)) == 1
+    assert L.hidet_probe_mfma_peak(hb.HIDET_F16, 24, 0x1000, 8192, 0x2000, n, None, ctypes.byref(f), ctypes.byref(f)) == 1
+    assert L.hidet_probe_mfma_peak(hb.HIDET_F16, 16, 0x1000, 8192, 0x2000, n - 1, None, ctypes.byref(f), ctypes.byref(f)) == 1
+    assert L.hidet_probe_mfma_peak(hb.HIDET_F16, 16, 0x1000, 8192, 0x2004, n, None, ctypes.byref(f), ctypes.byref(f)) == 3
+    assert L.hidet_probe_mfma_peak(9, 16, 0x1000, 8192, 0x2000, n, None, ctypes.byref(f), ctypes.byref(f)) == 1
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(hb, "_lib", None)
     monkeypatch.setattr(hb, "LIB_PATH", "/nonexistent/libhidet_mi355x.so")
