@@ -38,19 +38,31 @@ def side_report(torch, hb, wl, steps=200):
             return torch.from_numpy(np.ascontiguousarray(stored).view(np.int16)).view(torch.bfloat16).cuda()
         return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
 
-    def timed(fn, tune):
+    ws = torch.empty(16 << 20, dtype=torch.float32, device="cuda")  # 64 MiB: 16 K-slices of a 2^20-element output
+
+    def timed(fn, tune, tune_sliced=None, out_elems=0):
         # timed inside the library (a tight C++ launch loop between two HIP events): a Python call per
         # launch costs more than these small kernels run
         t0 = time.perf_counter()
         cfg, us = tune()
         tune_s = time.perf_counter() - t0
-        return us, cfg, tune_s
+        sliced = None
+        if tune_sliced is not None and out_elems <= (1 << 20):
+            # parallel reduction on K pays only when the output has few tiles; both kernels (partial sums and
+            # reduce + epilogue) are inside the timed launches
+            sliced = tune_sliced()
+        return us, cfg, tune_s, sliced
 
     rows = []
 
-    def add(name, dt, flops, nbytes, us, cfg, tune_s):
+    def add(name, dt, flops, nbytes, us, cfg, tune_s, sliced=None):
+        unsliced_us = us
+        slices = 1
+        if sliced is not None and sliced[2] < us:
+            cfg, slices, us = sliced
         info = hb.hidet_config_info(cfg)
-        rows.append({"workload": name, "dtype": dt, "us": round(us, 2), "TFLOPs": round(flops / us * 1e-6, 2),
+        rows.append({"workload": name, "dtype": dt, "us": round(us, 2), "k_slices": slices,
+                     "us_unsliced": round(unsliced_us, 2), "TFLOPs": round(flops / us * 1e-6, 2),
                      "pct_peak_mfma": round(100 * flops / us * 1e-6 / PEAK_TFLOPS[dt], 2),
                      "algorithmic_GBps": round(nbytes / us * 1e-3, 1), "pct_of_8TBps": round(100 * nbytes / us * 1e-3 / 8000, 2),
                      "tile_config": cfg, "tile": "%dx%dx%d/%dx%d/mfma%d" % (info["block_m"], info["block_n"], info["block_k"],
@@ -65,10 +77,11 @@ def side_report(torch, hb, wl, steps=200):
         C = torch.empty((c["M"], c["N"]), dtype=tdt[dt], device="cuda")
         axis = {None: hb.HIDET_BIAS_NONE, "col": hb.HIDET_BIAS_PER_COL, "row": hb.HIDET_BIAS_PER_ROW}[c["bias_axis"]]
         epi = hb.make_epilogue(alpha=c.get("alpha", 1.0), bias=bias, bias_axis=axis, residual=res, relu=c.get("relu", False))
-        us, cfg, ts = timed(lambda cfg: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg),
-                            lambda: hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=steps))
+        us, cfg, ts, sl = timed(lambda cfg: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg),
+                                lambda: hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=steps),
+                                lambda: hb.hidet_tune_gemm_splitk(A, B, C, ws, epilogue=epi, iters=steps), c["M"] * c["N"])
         nbytes = (c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] * (2 if res is not None else 1)) * es
-        add(c["name"], dt, 2.0 * c["M"] * c["N"] * c["K"], nbytes, us, cfg, ts)
+        add(c["name"], dt, 2.0 * c["M"] * c["N"] * c["K"], nbytes, us, cfg, ts, sl)
 
     for c in wl.config1():
         gemm_row(c)
@@ -80,21 +93,22 @@ def side_report(torch, hb, wl, steps=200):
         y = torch.empty((c["Nb"], c["OC"], c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
         epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
         sp = dict(stride=(c["stride"], c["stride"]), pad=(c["pad"], c["pad"]))
-        us, cfg, ts = timed(lambda cfg: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, config=cfg, **sp),
-                            lambda: hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp))
+        us, cfg, ts, sl = timed(lambda cfg: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, config=cfg, **sp),
+                                lambda: hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp),
+                                lambda: hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=steps, **sp), y.numel())
         flops = 2.0 * c["Nb"] * c["OC"] * c["OH"] * c["OW"] * c["IC"] * c["KH"] * c["KW"]
-        add(c["name"], "f16", flops, (x.numel() + w.numel() + y.numel()) * 2, us, cfg, ts)
+        add(c["name"], "f16", flops, (x.numel() + w.numel() + y.numel()) * 2, us, cfg, ts, sl)
     for c in wl.config4("f16"):
         Q, Kt, V, S = (dev(c[k], "f16") for k in ("Q", "K", "V", "S"))
         b, s, d = c["batch"], c["seq"], c["d"]
         scores = torch.empty((b, s, s), dtype=torch.float16, device="cuda")
         ctx = torch.empty((b, s, d), dtype=torch.float16, device="cuda")
         epi = hb.make_epilogue(alpha=c["alpha"])
-        us, cfg, ts = timed(lambda cfg: hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi, config=cfg),
-                            lambda: hb.hidet_tune_gemm(Q, Kt, scores, transB=True, epilogue=epi, iters=steps))
+        us, cfg, ts, _ = timed(lambda cfg: hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi, config=cfg),
+                               lambda: hb.hidet_tune_gemm(Q, Kt, scores, transB=True, epilogue=epi, iters=steps))
         add(c["name"] + "_QKt", "f16", 2.0 * b * s * s * d, (2 * b * s * d + b * s * s) * 2, us, cfg, ts)
-        us, cfg, ts = timed(lambda cfg: hb.hidet_batched_gemm(S, V, ctx, config=cfg),
-                            lambda: hb.hidet_tune_gemm(S, V, ctx, iters=steps))
+        us, cfg, ts, _ = timed(lambda cfg: hb.hidet_batched_gemm(S, V, ctx, config=cfg),
+                               lambda: hb.hidet_tune_gemm(S, V, ctx, iters=steps))
         add(c["name"] + "_SV", "f16", 2.0 * b * s * s * d, (2 * b * s * d + b * s * s) * 2, us, cfg, ts)
     for dt in ("f16", "bf16"):
         for K in (4096, 1024):

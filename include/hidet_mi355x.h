@@ -155,6 +155,58 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
                                  int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
                                  int64_t pad_w, const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
                                  void* stream, int32_t iters, int32_t* best_config, float* best_us);
+/*
+ * Parallel reduction on the K dimension (Section 5.2 and Section 6.3.4: the matrix-multiplication
+ * optimisation that the fused convolutions inherit, so that problems with few output tiles still fill
+ * the device).  K is cut into `k_slices` contiguous slices of whole K tiles; the grid grows by that
+ * factor; every workgroup accumulates one slice of one output tile and writes its fp32 partial tile
+ * into `workspace`; a second kernel sums the slices in ascending order in fp32 and applies the whole
+ * fused epilogue (alpha, bias, residual, ReLU) once, on the sum, then rounds to the output dtype.
+ * Results therefore differ from the unsliced call only by fp32 summation order.
+ *
+ *   workspace        DEVICE pointer, 16-byte aligned, caller-owned, at least
+ *                    hidet_splitk_workspace_bytes(batch, M, N, k_slices) bytes (for the convolution:
+ *                    batch = 1, M = OC, N = Nb*OH*OW); contents on entry ignored, clobbered on return;
+ *                    layout [batch][slice][M][N] fp32.  Calls that share a workspace must be ordered
+ *                    on one stream.
+ *   k_slices         > 1: requested slice count (the effective count may be smaller when K has fewer
+ *                    K tiles; with one effective slice the call runs the unsliced kernel and ignores
+ *                    the workspace); 1: unsliced; <= 0: take (config, k_slices) remembered by
+ *                    hidet_tune_*_splitk for this problem, else unsliced.
+ *   config           as for the *_cfg entry points; only configurations whose workgroup tile is at most
+ *                    128x128 have a sliced form, others return HIDET_ERR_NO_CONFIG when k_slices > 1.
+ *
+ * Errors: HIDET_ERR_INVALID_ARG if the workspace is NULL or too small for the effective slice count,
+ * HIDET_ERR_ALIGNMENT if it is misaligned, HIDET_ERR_UNSUPPORTED if batch > 65535 with slicing.
+ * hidet_splitk_workspace_bytes returns -1 for negative sizes or k_slices < 1.
+ */
+int64_t hidet_splitk_workspace_bytes(int64_t batch, int64_t M, int64_t N, int32_t k_slices);
+hidet_status_t hidet_batched_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int32_t transA,
+                                         int32_t transB, int64_t batch, int64_t M, int64_t N, int64_t K, const void* A,
+                                         int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
+                                         void* C, int64_t ldc, int64_t strideC, const hidet_epilogue_t* epi,
+                                         void* workspace, int64_t workspace_bytes, void* stream);
+hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int64_t Nb,
+                                                 int64_t IC, int64_t H, int64_t W, int64_t OC, int64_t KH, int64_t KW,
+                                                 int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                                 const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
+                                                 void* workspace, int64_t workspace_bytes, void* stream);
+/*
+ * Tuning over (configuration x k_slices in {1,2,3,4,6,8,12,16}) with the given workspace; slice
+ * counts the workspace cannot hold are skipped.  Otherwise as hidet_tune_gemm / hidet_tune_conv2d;
+ * the winner is remembered for the *_splitk entry points (k_slices <= 0, config < 0).
+ */
+hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
+                                      int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                                      int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                                      const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes, void* stream,
+                                      int32_t iters, int32_t* best_config, int32_t* best_slices, float* best_us);
+hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
+                                        int64_t OC, int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                        int64_t pad_h, int64_t pad_w, const void* x, const void* w, void* y,
+                                        const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes,
+                                        void* stream, int32_t iters, int32_t* best_config, int32_t* best_slices,
+                                        float* best_us);
 /* After a hidet_tune_* call: per-configuration mean microseconds of that run (negative = not applicable). */
 int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity);
 /* Forget every tuned entry. */

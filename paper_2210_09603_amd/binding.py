@@ -51,7 +51,8 @@ EXPORTS = (
     "hidet_conv2d_implicit_gemm_cfg", "hidet_config_count", "hidet_config_info", "hidet_tune_gemm", "hidet_tune_conv2d",
     "hidet_tune_last_times", "hidet_tune_clear", "hidet_tune_save", "hidet_tune_load", "hidet_taskmap_count",
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
-    "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes",
+    "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
+    "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk",
 )
 
 _lib = None
@@ -78,6 +79,14 @@ def lib():
         tune_tail = [_i32, ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_float)]
         L.hidet_tune_gemm.argtypes = bgemm_args + tune_tail
         L.hidet_tune_conv2d.argtypes = conv_args + tune_tail
+        L.hidet_splitk_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
+        L.hidet_splitk_workspace_bytes.restype = _i64
+        ws_args = [_vp, _i64, _vp]  # workspace, bytes, stream (replaces the trailing stream argument)
+        L.hidet_batched_gemm_splitk.argtypes = [_i32, _i32] + bgemm_args[:-1] + ws_args
+        L.hidet_conv2d_implicit_gemm_splitk.argtypes = [_i32, _i32] + conv_args[:-1] + ws_args
+        tune_tail_sk = [_i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_float)]
+        L.hidet_tune_gemm_splitk.argtypes = bgemm_args[:-1] + ws_args + tune_tail_sk
+        L.hidet_tune_conv2d_splitk.argtypes = conv_args[:-1] + ws_args + tune_tail_sk
         L.hidet_tune_last_times.argtypes = [ctypes.POINTER(ctypes.c_float), _i32]
         L.hidet_tune_clear.restype = None
         L.hidet_tune_save.argtypes = [ctypes.c_char_p]
@@ -225,6 +234,69 @@ def hidet_tune_conv2d(x, w, y, stride=(1, 1), pad=(0, 0), epilogue=None, stream=
                                  ctypes.byref(best), ctypes.byref(us))
     _check(st, "hidet_tune_conv2d")
     return best.value, us.value
+
+
+def hidet_splitk_workspace_bytes(batch, M, N, k_slices):
+    return lib().hidet_splitk_workspace_bytes(batch, M, N, k_slices)
+
+
+def _ws(workspace):
+    """(pointer, bytes) of a workspace tensor (any dtype, contiguous) or (NULL, 0)."""
+    if workspace is None:
+        return None, 0
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def hidet_batched_gemm_splitk(A, B, C, workspace, k_slices=0, transA=False, transB=False, epilogue=None, stream=None,
+                              config=-1):
+    """K-parallel form of hidet_batched_gemm (2-D tensors are taken as batch 1); workspace is a GPU tensor."""
+    if A.dim() == 2:
+        A, B, C = A.unsqueeze(0), B.unsqueeze(0), C.unsqueeze(0)
+    M, N, K = _gemm_dims(A, B, transA, transB)
+    batch = A.shape[0]
+    if B.shape[0] != batch or tuple(C.shape) != (batch, M, N):
+        raise ValueError("batch/shape mismatch")
+    wp, wb = _ws(workspace)
+    st = lib().hidet_batched_gemm_splitk(config, k_slices, _dtype(A), _dtype(C), int(transA), int(transB), batch, M, N, K,
+                                         _ptr(A), _ld(A), _bstride(A), _ptr(B), _ld(B), _bstride(B), _ptr(C), _ld(C),
+                                         _bstride(C), _epi_ref(epilogue), wp, wb, _stream(stream))
+    _check(st, "hidet_batched_gemm_splitk")
+
+
+def hidet_conv2d_implicit_gemm_splitk(x, w, y, workspace, k_slices=0, stride=(1, 1), pad=(0, 0), epilogue=None,
+                                      stream=None, config=-1):
+    """K-parallel form of hidet_conv2d_implicit_gemm; workspace is a GPU tensor."""
+    if tuple(y.shape) != conv_out_shape(x.shape, w.shape, stride, pad):
+        raise ValueError("y has the wrong shape")
+    wp, wb = _ws(workspace)
+    st = lib().hidet_conv2d_implicit_gemm_splitk(config, k_slices, *_conv_args(x, w, y, stride, pad), _epi_ref(epilogue),
+                                                 wp, wb, _stream(stream))
+    _check(st, "hidet_conv2d_implicit_gemm_splitk")
+
+
+def hidet_tune_gemm_splitk(A, B, C, workspace, transA=False, transB=False, epilogue=None, stream=None, iters=10):
+    """Enumerate configurations x slice counts; returns (best_config, best_slices, best_us)."""
+    if A.dim() == 2:
+        A, B, C = A.unsqueeze(0), B.unsqueeze(0), C.unsqueeze(0)
+    M, N, K = _gemm_dims(A, B, transA, transB)
+    batch = A.shape[0]
+    best, sl, us = _i32(-1), _i32(1), ctypes.c_float(0.0)
+    wp, wb = _ws(workspace)
+    st = lib().hidet_tune_gemm_splitk(_dtype(A), _dtype(C), int(transA), int(transB), batch, M, N, K, _ptr(A), _ld(A),
+                                      _bstride(A), _ptr(B), _ld(B), _bstride(B), _ptr(C), _ld(C), _bstride(C),
+                                      _epi_ref(epilogue), wp, wb, _stream(stream), iters, ctypes.byref(best),
+                                      ctypes.byref(sl), ctypes.byref(us))
+    _check(st, "hidet_tune_gemm_splitk")
+    return best.value, sl.value, us.value
+
+
+def hidet_tune_conv2d_splitk(x, w, y, workspace, stride=(1, 1), pad=(0, 0), epilogue=None, stream=None, iters=10):
+    best, sl, us = _i32(-1), _i32(1), ctypes.c_float(0.0)
+    wp, wb = _ws(workspace)
+    st = lib().hidet_tune_conv2d_splitk(*_conv_args(x, w, y, stride, pad), _epi_ref(epilogue), wp, wb, _stream(stream),
+                                        iters, ctypes.byref(best), ctypes.byref(sl), ctypes.byref(us))
+    _check(st, "hidet_tune_conv2d_splitk")
+    return best.value, sl.value, us.value
 
 
 def hidet_tune_last_times():

@@ -238,7 +238,15 @@ LaunchFn find_launcher(const Problem& pr, int config) {
 
 // Size-based default when the problem has not been tuned: the largest tile that still yields at
 // least one workgroup per compute unit, else the configuration with the most workgroups.
-int default_config(const Problem& pr) {
+LaunchFn find_partial_launcher(const Problem& pr, int config) {
+  if (config < 0 || config >= kNumConfigs) return nullptr;
+  const int variant = pr.op == 1 ? conv_variant(pr.elem_mode) : gemm_variant(pr.transA, pr.transB, pr.elem_mode);
+  return registry().fn[config][pr.dtype][kPartialVariants + variant];
+}
+
+// Untuned choice: the largest tile that still gives every compute unit a workgroup, else the tile
+// with the most workgroups.  With slices > 1 only tiles that have a K-parallel form take part.
+int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
   int best = -1;
   long long best_area = -1;
@@ -246,8 +254,9 @@ int default_config(const Problem& pr) {
   long long most_blocks = -1;
   for (int c = 0; c < kNumConfigs; ++c) {
     if (!find_launcher(pr, c)) continue;
+    if (slices > 1 && !find_partial_launcher(pr, c)) continue;
     const ConfigRow& r = kConfigs[c];
-    const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch;
+    const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch * (slices > 1 ? slices : 1);
     const long long area = (long long)r.bm * r.bn;
     if (blocks >= 256 && area > best_area) {
       best_area = area;
@@ -263,10 +272,14 @@ int default_config(const Problem& pr) {
 
 // ---- tuned-config cache ---------------------------------------------------------------------------
 std::mutex g_mutex;
-std::map<std::string, int> g_cache;
+struct Tuned {
+  int config;
+  int slices;
+};
+std::map<std::string, Tuned> g_cache;
 std::vector<float> g_last_times;
 
-std::string problem_key(const Problem& pr) {
+std::string problem_key(const Problem& pr, bool with_workspace = false) {
   char buf[256];
   const GemmParams& p = pr.p;
   const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0);
@@ -276,77 +289,153 @@ std::string problem_key(const Problem& pr) {
   else
     std::snprintf(buf, sizeof(buf), "conv:t%d:n%lld:c%d:%dx%d:o%lld:k%dx%d:s%dx%d:p%dx%d:e%d:m%d", pr.dtype, pr.Nb, p.g.IC,
                   p.g.H, p.g.W, pr.OC, p.g.KH, p.g.KW, p.g.sh, p.g.sw, p.g.ph, p.g.pw, epi_kind, pr.elem_mode);
-  return std::string(buf);
+  return std::string(buf) + (with_workspace ? ":ws" : "");
 }
 
-hidet_status_t launch(const Problem& pr_in, int config, hipStream_t stream) {
+struct SplitK {  // how the caller wants K parallelised
+  int slices = 1;            // requested number of K slices (<= 1: none); < 0 with a workspace: take the tuned value
+  void* workspace = nullptr;
+  long long workspace_bytes = 0;
+};
+
+template <int MAPPER>
+hipError_t reduce_dispatch(int dtype, const GemmParams& p, int batch, hipStream_t stream) {
+  switch (dtype) {
+    case HIDET_F32: return launch_reduce<float, MAPPER>(p, batch, stream);
+    case HIDET_F16: return launch_reduce<f16, MAPPER>(p, batch, stream);
+    default: return launch_reduce<bf16, MAPPER>(p, batch, stream);
+  }
+}
+
+hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStream_t stream) {
   Problem pr = pr_in;
   GemmParams& p = pr.p;
   if (pr.batch == 0 || p.M == 0 || p.N == 0) return HIDET_OK;
+  int slices = sk.slices;
   if (config < 0) {
     {
       std::lock_guard<std::mutex> lock(g_mutex);
-      auto it = g_cache.find(problem_key(pr));
-      if (it != g_cache.end()) config = it->second;
+      auto it = g_cache.find(problem_key(pr, sk.workspace != nullptr));
+      if (it != g_cache.end()) {
+        config = it->second.config;
+        if (slices < 0) slices = it->second.slices;
+      }
     }
-    if (config < 0 || !find_launcher(pr, config)) config = default_config(pr);
+    if (slices < 0) slices = 1;
+    if (config < 0 || !find_launcher(pr, config)) config = default_config(pr, slices);
   }
+  if (slices < 0) slices = 1;
   LaunchFn fn = find_launcher(pr, config);
   if (!fn) return HIDET_ERR_NO_CONFIG;
   const ConfigRow& r = kConfigs[config];
   p.tiles_m = (p.M + r.bm - 1) / r.bm;
   p.tiles_n = (p.N + r.bn - 1) / r.bn;
-  const long long total = (long long)p.tiles_m * p.tiles_n * pr.batch;
-  if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
-  p.total_blocks = (int)total;
   // grouped traversal: each run of 32 consecutive workgroups (one die's share of a 256-tile wave)
   // should cover a near-square patch of tiles
   p.group = p.tiles_m >= 4 ? 4 : p.tiles_m;
-  if (fn(p, stream) != hipSuccess) return HIDET_ERR_LAUNCH;
-  return HIDET_OK;
+  p.k_slices = 1;
+  p.k_slice_len = p.K;
+  long long len = p.K, actual = 1;
+  if (slices > 1 && p.K > 0) {
+    len = (p.K + slices - 1) / slices;
+    len = (len + r.bk - 1) / r.bk * r.bk;  // whole K tiles per slice keeps every slice 16-byte aligned
+    actual = (p.K + len - 1) / len;
+  }
+  if (actual <= 1) {
+    const long long total = (long long)p.tiles_m * p.tiles_n * pr.batch;
+    if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
+    p.total_blocks = (int)total;
+    if (fn(p, stream) != hipSuccess) return HIDET_ERR_LAUNCH;
+    return HIDET_OK;
+  }
+  // ---- parallel reduction on K: partial sums into the workspace, then reduce + epilogue
+  LaunchFn pfn = find_partial_launcher(pr, config);
+  if (!pfn) return HIDET_ERR_NO_CONFIG;
+  const long long need = 4LL * pr.batch * actual * p.M * p.N;
+  if (!sk.workspace || sk.workspace_bytes < need) return HIDET_ERR_INVALID_ARG;
+  if (!aligned(sk.workspace, 16)) return HIDET_ERR_ALIGNMENT;
+  if (pr.batch > 65535) return HIDET_ERR_UNSUPPORTED;
+  const long long total = (long long)p.tiles_m * p.tiles_n * pr.batch * actual;
+  if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
+  GemmParams q = p;
+  q.C = sk.workspace;
+  q.ldc = p.N;
+  q.strideC = (long long)p.M * p.N;
+  q.alpha = 1.0f;
+  q.bias = nullptr;
+  q.bias_axis = 0;
+  q.residual = nullptr;
+  q.relu = 0;
+  q.vec_store = (p.N % 4 == 0) ? 1 : 0;
+  q.k_slices = (int)actual;
+  q.k_slice_len = (int)len;
+  q.total_blocks = (int)total;
+  q.out_inner = 1;
+  q.out_outer = 0;
+  if (pfn(q, stream) != hipSuccess) return HIDET_ERR_LAUNCH;
+  GemmParams rp = p;
+  rp.A = sk.workspace;
+  rp.k_slices = (int)actual;
+  const hipError_t e = pr.op == 1 ? reduce_dispatch<MAP_NCHW>(pr.dtype, rp, (int)pr.batch, stream)
+                                  : reduce_dispatch<MAP_PLAIN>(pr.dtype, rp, (int)pr.batch, stream);
+  return e == hipSuccess ? HIDET_OK : HIDET_ERR_LAUNCH;
 }
 
-hidet_status_t tune(const Problem& pr, hipStream_t stream, int iters, int32_t* best_config, float* best_us) {
+const int kSliceChoices[] = {1, 2, 3, 4, 6, 8, 12, 16};
+
+// Enumerates the schedule space (x the K-slice choices when a workspace is given) on the caller's fused problem.
+hidet_status_t tune(const Problem& pr, const SplitK& sk, hipStream_t stream, int iters, int32_t* best_config,
+                    int32_t* best_slices, float* best_us) {
   if (iters <= 0) iters = 10;
   std::vector<float> times(kNumConfigs, -1.0f);
-  int best = -1;
+  int best = -1, best_sl = 1;
   float best_t = 0.0f;
   if (!(pr.batch == 0 || pr.p.M == 0 || pr.p.N == 0)) {
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return HIDET_ERR_LAUNCH;
     for (int c = 0; c < kNumConfigs; ++c) {
       if (!find_launcher(pr, c)) continue;
-      hidet_status_t st = launch(pr, c, stream);  // warm-up, also loads the code object
-      if (st != HIDET_OK) continue;
-      (void)hipEventRecord(e0, stream);
-      for (int i = 0; i < iters; ++i) launch(pr, c, stream);
-      (void)hipEventRecord(e1, stream);
-      if (hipEventSynchronize(e1) != hipSuccess) {
-        (void)hipEventDestroy(e0);
-        (void)hipEventDestroy(e1);
-        return HIDET_ERR_LAUNCH;
-      }
-      float ms = 0.0f;
-      (void)hipEventElapsedTime(&ms, e0, e1);
-      times[c] = ms * 1000.0f / (float)iters;
-      if (best < 0 || times[c] < best_t) {
-        best = c;
-        best_t = times[c];
+      for (int sl : kSliceChoices) {
+        if (sl > 1 && !sk.workspace) break;
+        SplitK one = sk;
+        one.slices = sl;
+        hidet_status_t st = launch(pr, c, one, stream);  // warm-up, also loads the code object
+        if (st != HIDET_OK) continue;
+        (void)hipEventRecord(e0, stream);
+        for (int i = 0; i < iters; ++i) launch(pr, c, one, stream);
+        (void)hipEventRecord(e1, stream);
+        if (hipEventSynchronize(e1) != hipSuccess) {
+          (void)hipEventDestroy(e0);
+          (void)hipEventDestroy(e1);
+          return HIDET_ERR_LAUNCH;
+        }
+        float ms = 0.0f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        const float us = ms * 1000.0f / (float)iters;
+        if (times[c] < 0.0f || us < times[c]) times[c] = us;
+        if (best < 0 || us < best_t) {
+          best = c;
+          best_sl = sl;
+          best_t = us;
+        }
       }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (best < 0) return HIDET_ERR_NO_CONFIG;
     // leave the winner's output in the buffer
-    launch(pr, best, stream);
+    SplitK win = sk;
+    win.slices = best_sl;
+    launch(pr, best, win, stream);
     (void)hipStreamSynchronize(stream);
   }
   {
     std::lock_guard<std::mutex> lock(g_mutex);
-    if (best >= 0) g_cache[problem_key(pr)] = best;
+    if (best >= 0) g_cache[problem_key(pr, sk.workspace != nullptr)] = Tuned{best, best_sl};
     g_last_times = times;
   }
   if (best_config) *best_config = best;
+  if (best_slices) *best_slices = best_sl;
   if (best_us) *best_us = best_t;
   return HIDET_OK;
 }
@@ -399,7 +488,7 @@ hidet_status_t hidet_batched_gemm_cfg(int32_t config, int32_t in, int32_t out, i
                                         C, ldc, strideC, epi);
   if (st != HIDET_OK) return st;
   if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
-  return launch(pr, config, (hipStream_t)stream);
+  return launch(pr, config, SplitK{}, (hipStream_t)stream);
 }
 
 hidet_status_t hidet_gemm_cfg(int32_t config, int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M,
@@ -433,7 +522,7 @@ hidet_status_t hidet_conv2d_implicit_gemm_cfg(int32_t config, int32_t in, int32_
                                         y, epi);
   if (st != HIDET_OK) return st;
   if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
-  return launch(pr, config, (hipStream_t)stream);
+  return launch(pr, config, SplitK{}, (hipStream_t)stream);
 }
 
 hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
@@ -474,7 +563,7 @@ hidet_status_t hidet_tune_gemm(int32_t in, int32_t out, int32_t transA, int32_t 
   hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
                                         C, ldc, strideC, epi);
   if (st != HIDET_OK) return st;
-  return tune(pr, (hipStream_t)stream, iters, best_config, best_us);
+  return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us);
 }
 
 hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W, int64_t OC,
@@ -485,7 +574,82 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
   hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
                                         y, epi);
   if (st != HIDET_OK) return st;
-  return tune(pr, (hipStream_t)stream, iters, best_config, best_us);
+  return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us);
+}
+
+// ---- K-parallel ("split-K") forms ------------------------------------------------------------------------------
+int64_t hidet_splitk_workspace_bytes(int64_t batch, int64_t M, int64_t N, int32_t k_slices) {
+  if (batch < 0 || M < 0 || N < 0 || k_slices < 1) return -1;
+  return 4 * batch * (int64_t)k_slices * M * N;
+}
+
+hidet_status_t hidet_batched_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int32_t transA,
+                                         int32_t transB, int64_t batch, int64_t M, int64_t N, int64_t K, const void* A,
+                                         int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
+                                         void* C, int64_t ldc, int64_t strideC, const hidet_epilogue_t* epi,
+                                         void* workspace, int64_t workspace_bytes, void* stream) {
+  Problem pr;
+  hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
+                                        C, ldc, strideC, epi);
+  if (st != HIDET_OK) return st;
+  if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  if (workspace_bytes < 0 || k_slices > 1024) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.slices = k_slices <= 0 ? -1 : k_slices;
+  sk.workspace = workspace;
+  sk.workspace_bytes = workspace_bytes;
+  return launch(pr, config, sk, (hipStream_t)stream);
+}
+
+hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int64_t Nb,
+                                                 int64_t IC, int64_t H, int64_t W, int64_t OC, int64_t KH, int64_t KW,
+                                                 int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                                 const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
+                                                 void* workspace, int64_t workspace_bytes, void* stream) {
+  Problem pr;
+  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
+                                        y, epi);
+  if (st != HIDET_OK) return st;
+  if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  if (workspace_bytes < 0 || k_slices > 1024) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.slices = k_slices <= 0 ? -1 : k_slices;
+  sk.workspace = workspace;
+  sk.workspace_bytes = workspace_bytes;
+  return launch(pr, config, sk, (hipStream_t)stream);
+}
+
+hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
+                                      int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                                      int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                                      const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes, void* stream,
+                                      int32_t iters, int32_t* best_config, int32_t* best_slices, float* best_us) {
+  Problem pr;
+  hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
+                                        C, ldc, strideC, epi);
+  if (st != HIDET_OK) return st;
+  if (!workspace || workspace_bytes <= 0) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.workspace = workspace;
+  sk.workspace_bytes = workspace_bytes;
+  return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us);
+}
+
+hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
+                                        int64_t OC, int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                        int64_t pad_h, int64_t pad_w, const void* x, const void* w, void* y,
+                                        const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes,
+                                        void* stream, int32_t iters, int32_t* best_config, int32_t* best_slices,
+                                        float* best_us) {
+  Problem pr;
+  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
+                                        y, epi);
+  if (st != HIDET_OK) return st;
+  if (!workspace || workspace_bytes <= 0) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.workspace = workspace;
+  sk.workspace_bytes = workspace_bytes;
+  return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us);
 }
 
 int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity) {
@@ -505,7 +669,7 @@ hidet_status_t hidet_tune_save(const char* path) {
   std::lock_guard<std::mutex> lock(g_mutex);
   FILE* f = std::fopen(path, "w");
   if (!f) return HIDET_ERR_INVALID_ARG;
-  for (const auto& kv : g_cache) std::fprintf(f, "%s %d\n", kv.first.c_str(), kv.second);
+  for (const auto& kv : g_cache) std::fprintf(f, "%s %d %d\n", kv.first.c_str(), kv.second.config, kv.second.slices);
   std::fclose(f);
   return HIDET_OK;
 }
@@ -515,10 +679,10 @@ hidet_status_t hidet_tune_load(const char* path) {
   FILE* f = std::fopen(path, "r");
   if (!f) return HIDET_ERR_INVALID_ARG;
   char key[256];
-  int cfg = 0;
+  int cfg = 0, slices = 1;
   std::lock_guard<std::mutex> lock(g_mutex);
-  while (std::fscanf(f, "%255s %d", key, &cfg) == 2)
-    if (cfg >= 0 && cfg < kNumConfigs) g_cache[std::string(key)] = cfg;
+  while (std::fscanf(f, "%255s %d %d", key, &cfg, &slices) == 3)
+    if (cfg >= 0 && cfg < kNumConfigs && slices >= 1 && slices <= 1024) g_cache[std::string(key)] = Tuned{cfg, slices};
   std::fclose(f);
   return HIDET_OK;
 }

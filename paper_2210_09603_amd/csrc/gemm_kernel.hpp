@@ -68,6 +68,8 @@ struct GemmParams {
   int vec_store;  // 1: groups of 4 consecutive output columns may use one vector access
   int tiles_m, tiles_n, group;
   int total_blocks;
+  int k_slices;     // > 1: parallel reduction on K -- workgroup z of a tile works on K range [z*k_slice_len, ...)
+  int k_slice_len;  // and writes raw fp32 partial sums to slice z of the workspace (C points at the workspace)
   ConvGeom g;           // img2col geometry (LD_IM2COL) and NCHW map (MAP_NCHW)
   long long out_inner;  // MAP_NCHW: OH*OW
   long long out_outer;  // MAP_NCHW: OC*OH*OW
@@ -261,56 +263,60 @@ struct Operand {
   const T* src;      // origin of this workgroup's panel: row r0 (KC) or column r0 (MC), k = 0
   long long ld;
   int rows_left;     // valid extent along ROWS from the panel origin (may exceed ROWS, may be <= 0)
-  int K;
+  int K;             // extent of this workgroup's K range
+  int kofs;          // global k index where that range starts (needed by the img2col gather)
   int r0;            // global row/column of the panel origin (needed by the img2col gather)
 
   // ---- global -> registers ------------------------------------------------------------------
   __device__ __forceinline__ u32x4 gather(int sr, int sc, int k0, const ConvGeom& g) const {
-    // element-by-element, zero-filled: any alignment, any edge
+    // Element by element, zero-filled: any alignment, any edge.  Every load is issued unconditionally
+    // from a clamped (always valid) address and the predicate is applied to the value, so the VEC loads
+    // of a chunk are in flight together instead of waiting for one another behind branches.
     T tmp[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) tmp[e] = (T)0.0f;
     if constexpr (MODE == LD_IM2COL) {
       // stored row sr = k index (ic, kh, kw), columns sc.. = output positions p (n, oh, ow)
-      const int k = k0 + sr;
-      if (k < K) {
-        const int khw = g.KH * g.KW;
-        const int ic = k / khw, rem = k - ic * khw;
-        const int kh = rem / g.KW, kw = rem - kh * g.KW;
-        const int ohw = g.OH * g.OW;
-        int p = r0 + sc;
-        int n = p / ohw;
-        int q = p - n * ohw;
-        int oh = q / g.OW, ow = q - oh * g.OW;
+      const int k = kofs + k0 + sr;
+      const bool k_ok = k0 + sr < K;
+      const int khw = g.KH * g.KW;
+      const int ic = k / khw, rem = k - ic * khw;
+      const int kh = rem / g.KW, kw = rem - kh * g.KW;
+      const int ohw = g.OH * g.OW;
+      const int p = r0 + sc;
+      int n = p / ohw;
+      const int q = p - n * ohw;
+      int oh = q / g.OW, ow = q - oh * g.OW;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          if (sc + e < rows_left) {
-            const int ih = oh * g.sh + kh - g.ph, iw = ow * g.sw + kw - g.pw;
-            if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
-              tmp[e] = src[(((long long)n * g.IC + ic) * g.H + ih) * g.W + iw];
-          }
-          if (++ow == g.OW) {
-            ow = 0;
-            if (++oh == g.OH) {
-              oh = 0;
-              ++n;
-            }
+      for (int e = 0; e < VEC; ++e) {
+        const int ih = oh * g.sh + kh - g.ph, iw = ow * g.sw + kw - g.pw;
+        const bool ok = k_ok && (sc + e < rows_left) && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+        const long long idx = ok ? (((long long)n * g.IC + ic) * g.H + ih) * g.W + iw : 0;
+        const T v = src[idx];
+        tmp[e] = ok ? v : (T)0.0f;
+        if (++ow == g.OW) {
+          ow = 0;
+          if (++oh == g.OH) {
+            oh = 0;
+            ++n;
           }
         }
       }
     } else if constexpr (LAYOUT == L_KC) {
-      if (sr < rows_left) {
-        const T* ptr = src + (long long)sr * ld + (k0 + sc);
+      const bool row_ok = sr < rows_left;
+      const long long base = row_ok ? (long long)sr * ld + (k0 + sc) : 0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
-          if (k0 + sc + e < K) tmp[e] = ptr[e];
+      for (int e = 0; e < VEC; ++e) {
+        const bool ok = row_ok && (k0 + sc + e < K);
+        const T v = src[ok ? base + e : 0];
+        tmp[e] = ok ? v : (T)0.0f;
       }
     } else {
-      if (k0 + sr < K) {
-        const T* ptr = src + (long long)(k0 + sr) * ld + sc;
+      const bool row_ok = k0 + sr < K;
+      const long long base = row_ok ? (long long)(k0 + sr) * ld + sc : 0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
-          if (sc + e < rows_left) tmp[e] = ptr[e];
+      for (int e = 0; e < VEC; ++e) {
+        const bool ok = row_ok && (sc + e < rows_left);
+        const T v = src[ok ? base + e : 0];
+        tmp[e] = ok ? v : (T)0.0f;
       }
     }
     return __builtin_bit_cast(u32x4, tmp);
@@ -547,7 +553,11 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
 // Pieces shared by the kernels.
 // ---------------------------------------------------------------------------------------------
 struct BlockCoords {
-  int batch, m0, n0;
+  int batch;    // batch entry whose A and B are used
+  int cbatch;   // index of the output matrix (batch entry, or batch * k_slices + slice for K-parallel partial sums)
+  int m0, n0;   // tile origin
+  int k_begin;  // K range of this workgroup
+  int k_len;
 };
 
 // Step 1, block-level task mapping.  Workgroups are handed to the 8 accelerator dies (XCDs)
@@ -560,9 +570,23 @@ __device__ __forceinline__ BlockCoords block_coords(const GemmParams& p) {
   const int per = total / 8, extra = total % 8;
   const int logical = xcd * per + (xcd < extra ? xcd : extra) + slot;
   const int tiles = p.tiles_m * p.tiles_n;
-  const int batch = logical / tiles;
-  const tmap::Task tile = tmap::GroupedSpatial{p.tiles_m, p.tiles_n, p.group}.task(logical - batch * tiles);
-  return BlockCoords{batch, tile.i * BM, tile.j * BN};
+  const int zb = logical / tiles;
+  const tmap::Task tile = tmap::GroupedSpatial{p.tiles_m, p.tiles_n, p.group}.task(logical - zb * tiles);
+  BlockCoords bc;
+  bc.cbatch = zb;
+  bc.m0 = tile.i * BM;
+  bc.n0 = tile.j * BN;
+  if (p.k_slices > 1) {
+    bc.batch = zb / p.k_slices;
+    bc.k_begin = (zb - bc.batch * p.k_slices) * p.k_slice_len;
+    const int left = p.K - bc.k_begin;
+    bc.k_len = left < p.k_slice_len ? left : p.k_slice_len;
+  } else {
+    bc.batch = zb;
+    bc.k_begin = 0;
+    bc.k_len = p.K;
+  }
+  return bc;
 }
 
 template <class Cfg, class OpA, class OpB>
@@ -570,18 +594,20 @@ __device__ __forceinline__ void setup_operands(const GemmParams& p, const BlockC
   using T = typename Cfg::T;
   const T* A = reinterpret_cast<const T*>(p.A) + (long long)bc.batch * p.strideA;
   const T* B = reinterpret_cast<const T*>(p.B) + (long long)bc.batch * p.strideB;
-  opa.src = (Cfg::LA == L_KC) ? A + (long long)bc.m0 * p.lda : A + bc.m0;
+  opa.src = (Cfg::LA == L_KC) ? A + (long long)bc.m0 * p.lda + bc.k_begin : A + (long long)bc.k_begin * p.lda + bc.m0;
   opa.ld = p.lda;
   opa.rows_left = p.M - bc.m0;
-  opa.K = p.K;
+  opa.K = bc.k_len;
+  opa.kofs = bc.k_begin;
   opa.r0 = bc.m0;
   if constexpr (Cfg::MODE_B == LD_IM2COL)
     opb.src = B;  // the gather addresses the whole input tensor
   else
-    opb.src = (Cfg::LB == L_KC) ? B + (long long)bc.n0 * p.ldb : B + bc.n0;
+    opb.src = (Cfg::LB == L_KC) ? B + (long long)bc.n0 * p.ldb + bc.k_begin : B + (long long)bc.k_begin * p.ldb + bc.n0;
   opb.ld = p.ldb;
   opb.rows_left = p.N - bc.n0;
-  opb.K = p.K;
+  opb.K = bc.k_len;
+  opb.kofs = bc.k_begin;
   opb.r0 = bc.n0;
 }
 
@@ -614,7 +640,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords&
                                          Acc (&acc)[Cfg::FM][Cfg::FN], const float (&col_bias)[4], unsigned char* smem) {
   using TO = typename Cfg::TO;
   constexpr int MI = Cfg::MI, FM = Cfg::FM, FN = Cfg::FN, WTN = Cfg::WTN;
-  TO* C = reinterpret_cast<TO*>(p.C) + (long long)bc.batch * p.strideC;
+  TO* C = reinterpret_cast<TO*>(p.C) + (long long)bc.cbatch * p.strideC;
   const TO* R = p.residual ? reinterpret_cast<const TO*>(p.residual) + (long long)bc.batch * p.strideR : nullptr;
   const TO* bias = reinterpret_cast<const TO*>(p.bias);
   constexpr int GROUPS = (MI == 32) ? 4 : 1;  // groups of 4 consecutive columns per accumulator tile
@@ -694,8 +720,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   load_col_bias<Cfg>(p, bc.n0 + wn0, lane, col_bias);
 
   // ---- steps 2 + 3: double-buffered main loop --------------------------------------------------
-  const int KT = (p.K + BK - 1) / BK;
-  const int KT_full = p.K / BK;  // tiles that lie entirely inside K
+  const int KT = (bc.k_len + BK - 1) / BK;
+  const int KT_full = bc.k_len / BK;  // tiles that lie entirely inside the K range
   u32x4 ra[OpA::NL], rb[OpB::NL];
   opa.init(tid);
   opb.init(tid);
@@ -894,7 +920,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
       __builtin_amdgcn_s_waitcnt(0x0070);
   };
 
-  const int S = p.K / BK;  // full stages
+  const int S = bc.k_len / BK;  // full stages
   if (S > 0) {
     opa.init_direct(tid);
     opb.init_direct(tid);
@@ -917,7 +943,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
     }
     if (grp == 0) phase_barrier();
   }
-  if (S * BK < p.K) {  // the partial last stage, through registers with zero fill
+  if (S * BK < bc.k_len) {  // the partial last stage, through registers with zero fill
     u32x4 ra[OpA::NL], rb[OpB::NL];
     opa.init(tid);
     opb.init(tid);
@@ -933,6 +959,48 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
   __syncthreads();  // the epilogue reuses the LDS
 
   epilogue<Cfg>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Parallel reduction on K, second pass (Sections 5.2 and 6.3.4: the matmul optimisation that lets
+// batch-1 convolutions fill the GPU): sums the fp32 partial results of the k_slices workgroups of
+// every output element and applies the fused epilogue.  p.A points at the workspace
+// [batch][k_slices][M][N]; p.C, bias, residual and the index map are those of the real output.
+// One thread per group of 4 consecutive columns.
+// ---------------------------------------------------------------------------------------------
+template <typename TO, int MAPPER>
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p) {
+  const int groups_per_row = (p.N + 3) / 4;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)p.M * groups_per_row) return;
+  const int m = (int)(idx / groups_per_row);
+  const int n = (int)(idx - (long long)m * groups_per_row) * 4;
+  const int batch = blockIdx.y;
+  const float* ws = reinterpret_cast<const float*>(p.A) + ((long long)batch * p.k_slices) * p.M * p.N + (long long)m * p.N + n;
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  const bool vec = (p.N % 4 == 0);
+  for (int z = 0; z < p.k_slices; ++z) {
+    const float* src = ws + (long long)z * p.M * p.N;
+    if (vec) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] += v[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < p.N) acc[e] += src[e];
+    }
+  }
+  float col_bias[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  const TO* bias = reinterpret_cast<const TO*>(p.bias);
+  if (p.bias_axis == 1) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (n + e < p.N) col_bias[e] = to_f32(bias[n + e]);
+  }
+  TO* C = reinterpret_cast<TO*>(p.C) + (long long)batch * p.strideC;
+  const TO* R = p.residual ? reinterpret_cast<const TO*>(p.residual) + (long long)batch * p.strideR : nullptr;
+  store4<TO, MAPPER>(p, C, R, bias, col_bias, m, n, acc);
 }
 
 }  // namespace hidet

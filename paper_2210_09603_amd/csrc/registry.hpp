@@ -11,7 +11,9 @@ using LaunchFn = hipError_t (*)(const GemmParams&, hipStream_t);
 
 constexpr int kMaxConfigs = 32;
 constexpr int kNumTypes = 3;     // index = hidet_dtype_t of the inputs: 0 f32, 1 f16, 2 bf16 (output has the same type)
-constexpr int kNumVariants = 10; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode
+constexpr int kNumVariants = 20; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode;
+                                 // +10: the same operand forms writing raw fp32 partial sums to a plain [M][N]
+                                 // workspace (first pass of the parallel reduction on K)
 
 struct ConfigRow {
   int index, bm, bn, bk, waves_m, waves_n, mfma, trans_a, sched, is_f32;
@@ -23,6 +25,7 @@ struct Registry {
 
 inline int gemm_variant(int transA, int transB, int elem_mode) { return (transA ? 4 : 0) + (transB ? 2 : 0) + (elem_mode ? 1 : 0); }
 inline int conv_variant(int elem_mode) { return 8 + (elem_mode ? 1 : 0); }
+constexpr int kPartialVariants = 10;  // offset of the K-parallel partial-sum kernels
 
 template <class Cfg>
 hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
@@ -51,6 +54,32 @@ void register_config(Registry& r, int index, int type_index) {
   // convolution: weights are a row-major OC x (IC*KH*KW) matrix, B is the img2col gather, C is NCHW
   v[conv_variant(0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_NCHW>>;
   v[conv_variant(1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_NCHW>>;
+  // K-parallel partial sums (fp32 out, plain map, general schedule): built for the small and medium tiles, which are
+  // the ones a problem with few output tiles and a long K wants
+  if constexpr (BM * BN <= 128 * 128) {
+    LaunchFn* w = v + kPartialVariants;
+    w[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+    w[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    w[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+    w[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    if constexpr (TRANS_A != 0) {
+      w[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+      w[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+      w[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+      w[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    }
+    w[conv_variant(0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_PLAIN>>;
+    w[conv_variant(1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_PLAIN>>;
+  }
+}
+
+// Second pass of the parallel reduction on K: [output type index][0 plain map, 1 NCHW map].
+template <typename TO, int MAPPER>
+hipError_t launch_reduce(const GemmParams& p, int batch, hipStream_t stream) {
+  const long long groups = (long long)p.M * ((p.N + 3) / 4);
+  hipLaunchKernelGGL((splitk_reduce_kernel<TO, MAPPER>), dim3((unsigned)((groups + 255) / 256), (unsigned)batch), dim3(256), 0,
+                     stream, p);
+  return hipGetLastError();
 }
 
 }  // namespace hidet

@@ -49,8 +49,15 @@ def oracle_bias_axis(axis):
     return oracle.BIAS_PER_ROW if axis == "row" else oracle.BIAS_PER_COL
 
 
-def run_gemm_case(c, config=-1, relu=None, alpha=None):
-    """Run one workloads.gemm_case through the HIP path and the oracle; returns (rel_error, got, ref)."""
+def make_workspace(batch, M, N, k_slices):
+    """fp32 workspace of the K-parallel entry points, filled with NaN so that a stale read shows."""
+    n = hb.hidet_splitk_workspace_bytes(batch, M, N, max(k_slices, 1)) // 4
+    return torch.full((max(n, 4),), float("nan"), dtype=torch.float32, device="cuda")
+
+
+def run_gemm_case(c, config=-1, relu=None, alpha=None, k_slices=None):
+    """Run one workloads.gemm_case through the HIP path and the oracle; returns (rel_error, got, ref).
+    With k_slices the K-parallel entry point runs instead of the plain one."""
     dt = c["dtype"]
     relu = c.get("relu", False) if relu is None else relu
     alpha = c.get("alpha", 1.0) if alpha is None else alpha
@@ -61,7 +68,11 @@ def run_gemm_case(c, config=-1, relu=None, alpha=None):
     bias, res = to_gpu(c["bias"], dt), to_gpu(c["residual"], dt)
     C = torch.full((M, N), float("nan"), dtype=TORCH_DTYPE[dt], device="cuda")
     epi = hb.make_epilogue(alpha=alpha, bias=bias, bias_axis=bias_axis_code(c["bias_axis"]), residual=res, relu=relu)
-    hb.hidet_gemm(Av, Bv, C, transA=c["transA"], transB=c["transB"], epilogue=epi, config=config)
+    if k_slices is None:
+        hb.hidet_gemm(Av, Bv, C, transA=c["transA"], transB=c["transB"], epilogue=epi, config=config)
+    else:
+        hb.hidet_batched_gemm_splitk(Av, Bv, C, make_workspace(1, M, N, k_slices), k_slices=k_slices, transA=c["transA"],
+                                     transB=c["transB"], epilogue=epi, config=config)
     torch.cuda.synchronize()
     A64 = wl.widen(c["A"], dt)
     B64 = wl.widen(c["B"], dt)
@@ -75,7 +86,7 @@ def run_gemm_case(c, config=-1, relu=None, alpha=None):
     return oracle.rel_frobenius(got, ref), got, ref
 
 
-def run_conv_case(c, config=-1):
+def run_conv_case(c, config=-1, k_slices=None):
     dt = c["dtype"]
     x, w = to_gpu(c["x"], dt), to_gpu(c["w"], dt)
     bias, res = to_gpu(c["bias"], dt), to_gpu(c["residual"], dt)
@@ -85,13 +96,24 @@ def run_conv_case(c, config=-1):
     y = torch.full(hb.conv_out_shape(x.shape, w.shape, stride, pad), float("nan"), dtype=TORCH_DTYPE[dt], device="cuda")
     epi = hb.make_epilogue(alpha=c.get("alpha", 1.0), bias=bias, bias_axis=hb.HIDET_BIAS_PER_ROW, residual=res,
                            relu=c.get("relu", False))
-    hb.hidet_conv2d_implicit_gemm(x, w, y, stride=stride, pad=pad, epilogue=epi, config=config)
+    if k_slices is None:
+        hb.hidet_conv2d_implicit_gemm(x, w, y, stride=stride, pad=pad, epilogue=epi, config=config)
+    else:
+        ws = make_workspace(1, y.shape[1], y.shape[0] * y.shape[2] * y.shape[3], k_slices)
+        hb.hidet_conv2d_implicit_gemm_splitk(x, w, y, ws, k_slices=k_slices, stride=stride, pad=pad, epilogue=epi,
+                                             config=config)
     torch.cuda.synchronize()
     ref = oracle.conv2d(wl.widen(c["x"], dt), wl.widen(c["w"], dt), stride=stride, pad=pad, alpha=c.get("alpha", 1.0),
                         bias=None if c["bias"] is None else wl.widen(c["bias"], dt),
                         residual=None if c["residual"] is None else wl.widen(c["residual"], dt), relu=c.get("relu", False))
     got = to_f64(y)
     return oracle.rel_frobenius(got, ref), got, ref
+
+
+def sliceable_configs(dtype):
+    """Configurations that have a K-parallel form (workgroup tile at most 128x128)."""
+    return [i for i in applicable_configs(dtype)
+            if hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128]
 
 
 def applicable_configs(dtype):

@@ -7,7 +7,8 @@ import oracle
 from paper_2210_09603_amd import binding as hb
 from paper_2210_09603_amd import workloads as wl
 
-from helpers import TOL, TORCH_DTYPE, applicable_configs, run_conv_case, run_gemm_case, to_f64, to_gpu, within_bound
+from helpers import (TOL, TORCH_DTYPE, applicable_configs, make_workspace, run_conv_case, run_gemm_case, sliceable_configs,
+                     to_f64, to_gpu, within_bound)
 
 pytestmark = pytest.mark.gpu
 
@@ -243,13 +244,142 @@ def test_tuner_enumerates_the_space_and_caches(tmp_path):
     path = str(tmp_path / "tuned.txt")
     hb.hidet_tune_save(path)
     text = open(path).read()
-    assert "gemm:t1:00:b1:128x768x256" in text and text.strip().endswith(str(best))
+    assert "gemm:t1:00:b1:128x768x256" in text and text.strip().endswith("%d 1" % best)
     hb.hidet_tune_clear()
     hb.hidet_tune_load(path)
     C.zero_()
     hb.hidet_gemm(A, B, C, epilogue=epi)
     torch.cuda.synchronize()
     assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ parallel reduction on K
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_splitk_every_sliceable_config(dtype):
+    cfgs = sliceable_configs(dtype)
+    assert cfgs
+    for cfg in cfgs:
+        for tB, slices in ((False, 2), (True, 5)):
+            # ragged everything: K = 1203 leaves a short last slice and a partial K tile inside it
+            c = wl.gemm_case(8200 + cfg, 155, 203, 1203, dtype, transB=tB, bias="col", residual=True)
+            err, _, _ = run_gemm_case(c, config=cfg, relu=True, alpha=0.75, k_slices=slices)
+            _say("splitk config %d %s tB%d slices %d err %.3e" % (cfg, dtype, tB, slices, err))
+            assert err <= TOL[dtype], cfg
+        c = wl.gemm_case(8300 + cfg, 136, 200, 1024, dtype, bias="row")  # aligned: vector loads and stores
+        err, _, _ = run_gemm_case(c, config=cfg, k_slices=4)
+        assert err <= TOL[dtype], cfg
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_splitk_conv_every_sliceable_config(dtype):
+    for cfg in sliceable_configs(dtype):
+        c = wl.conv_case(8400 + cfg, 2, 37, 11, 9, 7, 3, 3, 2, 1, dtype, residual=True)  # K = 333
+        c.update(relu=True)
+        err, _, _ = run_conv_case(c, config=cfg, k_slices=3)
+        _say("splitk conv config %d %s err %.3e" % (cfg, dtype, err))
+        assert err <= TOL[dtype], cfg
+    c = wl.conv_case(8450, 1, 64, 14, 14, 32, 3, 3, 1, 1, dtype)  # aligned weights: vector loads on A
+    c.update(relu=True)
+    for slices in (2, 8):
+        err, _, _ = run_conv_case(c, config=sliceable_configs(dtype)[0], k_slices=slices)
+        assert err <= TOL[dtype]
+
+
+def test_splitk_transposed_a_and_default_config():
+    for tA, tB in ((True, False), (True, True)):
+        c = wl.gemm_case(8500, 72, 88, 900, "f16", transA=tA, transB=tB, residual=True)
+        err, _, _ = run_gemm_case(c, k_slices=6)  # config -1: nothing tuned, the default tile must be sliceable or refuse
+        assert err <= TOL["f16"]
+
+
+def test_splitk_is_exact_on_integer_data_and_equals_the_unsliced_result():
+    """Small integers: every partial sum is exact in fp32, so slicing K cannot change a single bit."""
+    g = np.random.default_rng(8600)
+    A = torch.from_numpy(g.integers(-3, 4, (96, 1536)).astype(np.float32)).cuda()
+    B = torch.from_numpy(g.integers(-3, 4, (1536, 80)).astype(np.float32)).cuda()
+    exact = (A.double().cpu() @ B.double().cpu())
+    cfg = sliceable_configs("f32")[0]
+    for slices in (1, 2, 7, 16):
+        C = torch.full((96, 80), float("nan"), dtype=torch.float32, device="cuda")
+        hb.hidet_batched_gemm_splitk(A, B, C, make_workspace(1, 96, 80, slices), k_slices=slices, config=cfg)
+        torch.cuda.synchronize()
+        assert torch.equal(C.cpu().double(), exact), slices
+
+
+def test_splitk_degenerate_slice_counts_and_workspace_extent():
+    c = wl.gemm_case(8700, 40, 56, 40, "f16", bias="col")
+    cfg = sliceable_configs("f16")[0]
+    # more slices than K tiles: the effective count shrinks (possibly to one: the unsliced kernel)
+    err, _, _ = run_gemm_case(c, config=cfg, k_slices=16)
+    assert err <= TOL["f16"]
+    # K = 0 with slices: C = epilogue(0), workspace unused
+    bias = torch.tensor([1.0, -2.0, 3.0, 0.5], dtype=torch.float16, device="cuda")
+    C = torch.full((4, 4), float("nan"), dtype=torch.float16, device="cuda")
+    hb.hidet_batched_gemm_splitk(torch.zeros((4, 0), dtype=torch.float16, device="cuda"),
+                                 torch.zeros((0, 4), dtype=torch.float16, device="cuda"), C, None, k_slices=4,
+                                 epilogue=hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True))
+    torch.cuda.synchronize()
+    assert torch.equal(C.cpu(), torch.tensor([[1.0, 0.0, 3.0, 0.5]] * 4, dtype=torch.float16))
+    # the kernels stay inside the stated workspace size and inside C
+    c = wl.gemm_case(8710, 45, 51, 700, "f16")
+    A, B = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16")
+    need = hb.hidet_splitk_workspace_bytes(1, 45, 51, 4) // 4
+    ws = torch.full((need + 1024,), 5.0, dtype=torch.float32, device="cuda")
+    big = torch.full((64, 64), 7.0, dtype=torch.float16, device="cuda")
+    hb.hidet_batched_gemm_splitk(A, B, big[:45, :51], ws[:need], k_slices=4, config=cfg)
+    torch.cuda.synchronize()
+    assert torch.all(ws[need:] == 5.0)
+    assert torch.all(big[45:, :] == 7.0) and torch.all(big[:, 51:] == 7.0)
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"))
+    assert oracle.rel_frobenius(to_f64(big[:45, :51]), ref) <= TOL["f16"]
+    # too small a workspace is refused, not overrun
+    with pytest.raises(hb.HidetError):
+        hb.hidet_batched_gemm_splitk(A, B, big[:45, :51], ws[:need - 1], k_slices=4, config=cfg)
+
+
+def test_splitk_batched_with_shared_operand_and_residual():
+    g = wl.rng(8800)
+    A = wl.normal(g, (5, 33, 640), "f16")
+    B = wl.normal(g, (640, 29), "f16")
+    R = wl.normal(g, (5, 33, 29), "f16")
+    dA, dB, dR = to_gpu(A, "f16"), to_gpu(B, "f16"), to_gpu(R, "f16")
+    C = torch.zeros((5, 33, 29), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(alpha=0.25, residual=dR, relu=True, batched=True)
+    hb.hidet_batched_gemm_splitk(dA, dB.unsqueeze(0).expand(5, 640, 29), C, make_workspace(5, 33, 29, 3), k_slices=3,
+                                 epilogue=epi)
+    torch.cuda.synchronize()
+    ref = oracle.batched_gemm(wl.widen(A, "f16"), np.broadcast_to(wl.widen(B, "f16"), (5, 640, 29)), alpha=0.25,
+                              residual=wl.widen(R, "f16"), relu=True)
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+
+
+def test_splitk_tuner_picks_slices_for_a_few_tile_problem():
+    # the small transformer product: 6 x 1 tiles of 128x128 cannot fill 256 compute units without slicing K
+    c = wl.gemm_case(8900, 128, 768, 3072, "f16", bias="col")
+    A, B, bias = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16"), to_gpu(c["bias"], "f16")
+    C = torch.zeros((128, 768), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL)
+    ws = make_workspace(1, 128, 768, 16)
+    hb.hidet_tune_clear()
+    best, slices, us = hb.hidet_tune_gemm_splitk(A, B, C, ws, epilogue=epi, iters=5)
+    _say("splitk tuner: config %d slices %d %.1f us" % (best, slices, us))
+    assert best in applicable_configs("f16") and slices in (1, 2, 3, 4, 6, 8, 12, 16)
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"), bias=wl.widen(c["bias"], "f16"))
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+    C.zero_()
+    hb.hidet_batched_gemm_splitk(A, B, C, ws, k_slices=0, epilogue=epi)  # remembered (config, slices)
+    torch.cuda.synchronize()
+    assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
+    x = wl.conv_case(8910, 1, 256, 14, 14, 256, 3, 3, 1, 1, "f16")
+    x.update(relu=True)
+    dx, dw, db = to_gpu(x["x"], "f16"), to_gpu(x["w"], "f16"), to_gpu(x["bias"], "f16")
+    y = torch.zeros((1, 256, 14, 14), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(bias=db, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+    best, slices, us = hb.hidet_tune_conv2d_splitk(dx, dw, y, ws, stride=(1, 1), pad=(1, 1), epilogue=epi, iters=5)
+    _say("splitk conv tuner: config %d slices %d %.1f us" % (best, slices, us))
+    ref = oracle.conv2d(wl.widen(x["x"], "f16"), wl.widen(x["w"], "f16"), stride=(1, 1), pad=(1, 1),
+                        bias=wl.widen(x["bias"], "f16"), relu=True)
+    assert oracle.rel_frobenius(to_f64(y), ref) <= TOL["f16"]
 
 
 # ------------------------------------------------------------------ measurement aid

@@ -118,6 +118,45 @@ def test_batched_and_conv_argument_validation():
     assert hb.lib().hidet_status_string(3) == b"misaligned pointer"
 
 
+def test_splitk_argument_validation():
+    """Fake pointers again: every call must be turned down on the host."""
+    L = hb.lib()
+    f16 = hb.HIDET_F16
+    assert L.hidet_splitk_workspace_bytes(2, 3, 5, 4) == 4 * 2 * 4 * 3 * 5
+    assert L.hidet_splitk_workspace_bytes(1, 64, 64, 1) == 4 * 64 * 64
+    assert L.hidet_splitk_workspace_bytes(1, 64, 64, 0) == -1
+    assert L.hidet_splitk_workspace_bytes(-1, 64, 64, 2) == -1
+    sliceable = [i for i in range(hb.hidet_config_count())
+                 if not hb.hidet_config_info(i)["is_f32"]
+                 and hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128][0]
+    need = 4 * 4 * 64 * 64
+
+    def g(config=sliceable, slices=4, ws=0x10000, ws_bytes=need, K=1024, A=0x1000):
+        return L.hidet_batched_gemm_splitk(config, slices, f16, f16, 0, 0, 1, 64, 64, K, A, K, 0, 0x2000, 64, 0, 0x3000,
+                                           64, 0, None, ws, ws_bytes, None)
+    assert g(ws=None) == 1
+    assert g(ws_bytes=need - 4) == 1
+    assert g(ws_bytes=-1) == 1
+    assert g(ws=0x10004) == 3
+    assert g(slices=5000) == 1
+    assert g(A=None) == 1  # the ordinary validation still comes first
+    assert g(config=10 ** 6) == 4
+    big = [i for i in range(hb.hidet_config_count()) if hb.hidet_config_info(i)["block_m"] == 256
+           and not hb.hidet_config_info(i)["is_f32"]][0]
+    assert g(config=big) == 4  # large tiles have no K-parallel form
+
+    def c(slices=4, ws=0x10000, ws_bytes=4 * 4 * 8 * 64, x=0x1000):
+        return L.hidet_conv2d_implicit_gemm_splitk(sliceable, slices, f16, f16, 1, 64, 8, 8, 8, 3, 3, 1, 1, 1, 1, x,
+                                                   0x2000, 0x3000, None, ws, ws_bytes, None)
+    assert c(ws=None) == 1
+    assert c(ws_bytes=64) == 1
+    assert c(x=None) == 1
+    f = ctypes.c_float()
+    i = ctypes.c_int32()
+    assert L.hidet_tune_gemm_splitk(f16, f16, 0, 0, 1, 64, 64, 1024, 0x1000, 1024, 0, 0x2000, 64, 0, 0x3000, 64, 0, None,
+                                    None, 0, None, 3, ctypes.byref(i), ctypes.byref(i), ctypes.byref(f)) == 1
+
+
 def test_probe_argument_validation():
     L = hb.lib()
     n = L.hidet_probe_scratch_bytes()
