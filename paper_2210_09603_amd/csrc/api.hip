@@ -187,8 +187,10 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   const long long OH = (H + 2 * ph - KH) >= 0 ? (H + 2 * ph - KH) / sh + 1 : 0;
   const long long OW = (W + 2 * pw - KW) >= 0 ? (W + 2 * pw - KW) / sw + 1 : 0;
   const long long M = OC, N = Nb * OH * OW, K = IC * KH * KW;
-  if (M > kIntMax || N > kIntMax || K > kIntMax || Nb * IC * H * W > kIntMax || H + 2 * ph > 1000000 ||
-      W + 2 * pw > 1000000)
+  // the gather keeps input rows and columns (padding included) in signed 16-bit fields and element
+  // offsets in 32 bits
+  if (M > kIntMax || N > kIntMax || K > kIntMax || Nb * IC * H * W > kIntMax || H + 2 * ph > 32767 ||
+      W + 2 * pw > 32767 || KH > 32767 || KW > 32767)
     return HIDET_ERR_UNSUPPORTED;
   const bool empty = (M == 0 || N == 0);
   if (!empty) {
@@ -218,7 +220,9 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   fill_epilogue(p, epi);
   p.ldr = 0;
   p.strideR = 0;
-  p.g = ConvGeom{(int)IC, (int)H, (int)W, (int)KH, (int)KW, (int)sh, (int)sw, (int)ph, (int)pw, (int)OH, (int)OW};
+  p.g = ConvGeom{(int)IC, (int)H, (int)W, (int)KH, (int)KW, (int)sh, (int)sw, (int)ph, (int)pw, (int)OH, (int)OW,
+                 make_fastdiv(KH * KW), make_fastdiv(KW), make_fastdiv(OH * OW > 0 ? OH * OW : 1),
+                 make_fastdiv(OW > 0 ? OW : 1)};
   p.out_inner = OH * OW;
   p.out_outer = OC * OH * OW;
   const int vec = 16 / elem_size(in);

@@ -49,8 +49,35 @@ enum : int { LD_VEC = 0, LD_ELEM = 1, LD_IM2COL = 2 };  // how a chunk is fetche
 enum : int { MAP_PLAIN = 0, MAP_NCHW = 1 };           // output index map
 enum : int { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1 };  // main-loop schedule
 
+// Division of a non-negative 31-bit integer by a divisor fixed at launch: floor(n / d) =
+// (n * mul) >> shift with mul = ceil(2^shift / d), shift = 31 + ceil(log2 d), which is exact for
+// every 0 <= n < 2^31 (Granlund and Montgomery, "Division by invariant integers using
+// multiplication", Theorem 4.2).  Two instructions instead of the forty-odd of a hardware-less
+// 32-bit division; the img2col gather divides for every chunk it fetches.
+struct FastDiv {
+  unsigned int mul;
+  unsigned int shift;
+#if defined(__HIPCC__)
+  __host__ __device__
+#endif
+  int div(int n) const {
+    return (int)(((unsigned long long)(unsigned int)n * mul) >> shift);
+  }
+};
+
+inline FastDiv make_fastdiv(long long d) {
+  FastDiv f;
+  unsigned int l = 0;
+  while ((1LL << l) < d) ++l;
+  f.shift = 31 + l;
+  const unsigned __int128 one = 1;
+  f.mul = (unsigned int)(((one << f.shift) + (unsigned __int128)d - 1) / (unsigned __int128)d);
+  return f;
+}
+
 struct ConvGeom {
   int IC, H, W, KH, KW, sh, sw, ph, pw, OH, OW;
+  FastDiv d_khw, d_kw, d_ohw, d_ow;  // dividers by KH*KW, KW, OH*OW, OW
 };
 
 struct GemmParams {
@@ -268,37 +295,28 @@ struct Operand {
   int r0;            // global row/column of the panel origin (needed by the img2col gather)
 
   // ---- global -> registers ------------------------------------------------------------------
-  __device__ __forceinline__ u32x4 gather(int sr, int sc, int k0, const ConvGeom& g) const {
+  __device__ __forceinline__ u32x4 gather(int q, int sr, int sc, int k0, const ConvGeom& g) const {
     // Element by element, zero-filled: any alignment, any edge.  Every load is issued unconditionally
     // from a clamped (always valid) address and the predicate is applied to the value, so the VEC loads
     // of a chunk are in flight together instead of waiting for one another behind branches.
     T tmp[VEC];
     if constexpr (MODE == LD_IM2COL) {
-      // stored row sr = k index (ic, kh, kw), columns sc.. = output positions p (n, oh, ow)
-      const int k = kofs + k0 + sr;
-      const bool k_ok = k0 + sr < K;
-      const int khw = g.KH * g.KW;
-      const int ic = k / khw, rem = k - ic * khw;
-      const int kh = rem / g.KW, kw = rem - kh * g.KW;
-      const int ohw = g.OH * g.OW;
-      const int p = r0 + sc;
-      int n = p / ohw;
-      const int q = p - n * ohw;
-      int oh = q / g.OW, ow = q - oh * g.OW;
+      // stored row sr = k index (ic, kh, kw), columns sc.. = output positions p (n, oh, ow).  The part
+      // that depends on p does not change from one K tile to the next and was prepared by init().
+      const int kk = k0 + sr;
+      const int k = kofs + kk;
+      const int ic = g.d_khw.div(k), rem = k - ic * (g.KH * g.KW);
+      const int kh = g.d_kw.div(rem), kw = rem - kh * g.KW;
+      const int koff = (ic * g.H + kh) * g.W + kw;
+      const int khv = kk < K ? kh : -(1 << 20);  // beyond the K range: every row test below fails
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const int ih = oh * g.sh + kh - g.ph, iw = ow * g.sw + kw - g.pw;
-        const bool ok = k_ok && (sc + e < rows_left) && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
-        const long long idx = ok ? (((long long)n * g.IC + ic) * g.H + ih) * g.W + iw : 0;
+        const int xy = pxy[q * VEC + e];
+        const int ih = (int)(short)(xy & 0xffff) + khv, iw = (xy >> 16) + kw;
+        const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+        const int idx = ok ? pofs[q * VEC + e] + koff : 0;
         const T v = src[idx];
         tmp[e] = ok ? v : (T)0.0f;
-        if (++ow == g.OW) {
-          ow = 0;
-          if (++oh == g.OH) {
-            oh = 0;
-            ++n;
-          }
-        }
       }
     } else if constexpr (LAYOUT == L_KC) {
       const bool row_ok = sr < rows_left;
@@ -328,8 +346,38 @@ struct Operand {
   // rows or columns that are never stored, so any finite or non-finite value is harmless there.
   // Along K a chunk outside the matrix must read as zero; that can only happen in the last K tile.
   int off[NL];  // element offset of each chunk from `src` at k = 0 (vector mode only)
+  // img2col mode only, per fetched element: offset of input pixel (n, oh*sh - ph, ow*sw - pw) of channel 0
+  // from `src` (may be negative), and that pixel's row and column packed as two signed 16-bit fields
+  // (row -32768 marks an output position outside the matrix).
+  static constexpr int NP = (MODE == LD_IM2COL) ? NL * VEC : 1;
+  int pofs[NP];
+  int pxy[NP];
 
-  __device__ __forceinline__ void init(int tid) {
+  __device__ __forceinline__ void init(int tid, const ConvGeom& g) {
+    if constexpr (MODE == LD_IM2COL) {
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        const int sc = t.j * VEC;
+        const int p = r0 + sc;
+        int n = g.d_ohw.div(p);
+        const int r = p - n * (g.OH * g.OW);
+        int oh = g.d_ow.div(r), ow = r - oh * g.OW;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
+          pofs[q * VEC + e] = (n * g.IC * g.H + ih0) * g.W + iw0;
+          pxy[q * VEC + e] = (sc + e < rows_left) ? ((ih0 & 0xffff) | (iw0 << 16)) : 0x8000;
+          if (++ow == g.OW) {
+            ow = 0;
+            if (++oh == g.OH) {
+              oh = 0;
+              ++n;
+            }
+          }
+        }
+      }
+    }
     if constexpr (MODE == LD_VEC) {
 #pragma unroll
       for (int q = 0; q < NL; ++q) {
@@ -403,7 +451,7 @@ struct Operand {
         if (inside) v = *reinterpret_cast<const u32x4*>(base + off[q]);
         regs[q] = v;
       } else {
-        regs[q] = gather(sr, sc, k0, g);
+        regs[q] = gather(q, sr, sc, k0, g);
       }
     }
   }
@@ -468,6 +516,13 @@ struct Operand {
   }
 };
 
+// Output index map of the convolution: GEMM element (m, n) = (output channel, image * OH*OW + pixel)
+// lives at [image][m][pixel] of the NCHW tensor.
+__device__ __forceinline__ long long nchw_offset(const GemmParams& p, int m, int n) {
+  const int img = p.g.d_ohw.div(n);
+  return (long long)img * p.out_outer + (long long)m * p.out_inner + (n - img * (int)p.out_inner);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fused epilogue + predicated store of 4 consecutive output columns of one row.
 // ---------------------------------------------------------------------------------------------
@@ -481,8 +536,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     off = (long long)m * p.ldc + n;
     roff = (long long)m * p.ldr + n;
   } else {
-    const long long img = n / p.out_inner;
-    off = img * p.out_outer + (long long)m * p.out_inner + (n - img * p.out_inner);
+    off = nchw_offset(p, m, n);
     roff = off;
   }
   float v[4];
@@ -511,10 +565,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
       for (int e = 0; e < 4; ++e) {
         if (n + e < p.N) {
           long long ro = roff + e;
-          if constexpr (MAPPER == MAP_NCHW) {
-            const long long img = (n + e) / p.out_inner;
-            ro = img * p.out_outer + (long long)m * p.out_inner + ((n + e) - img * p.out_inner);
-          }
+          if constexpr (MAPPER == MAP_NCHW) ro = nchw_offset(p, m, n + e);
           v[e] += to_f32(R[ro]);
         }
       }
@@ -539,10 +590,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     for (int e = 0; e < 4; ++e) {
       if (n + e < p.N) {
         long long oo = off + e;
-        if constexpr (MAPPER == MAP_NCHW) {
-          const long long img = (n + e) / p.out_inner;
-          oo = img * p.out_outer + (long long)m * p.out_inner + ((n + e) - img * p.out_inner);
-        }
+        if constexpr (MAPPER == MAP_NCHW) oo = nchw_offset(p, m, n + e);
         C[oo] = o[e];
       }
     }
@@ -723,8 +771,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   const int KT = (bc.k_len + BK - 1) / BK;
   const int KT_full = bc.k_len / BK;  // tiles that lie entirely inside the K range
   u32x4 ra[OpA::NL], rb[OpB::NL];
-  opa.init(tid);
-  opb.init(tid);
+  opa.init(tid, p.g);
+  opb.init(tid, p.g);
 
   auto fetch = [&](int kt) {  // global -> registers
     if (kt < KT_full) {
@@ -945,8 +993,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
   }
   if (S * BK < bc.k_len) {  // the partial last stage, through registers with zero fill
     u32x4 ra[OpA::NL], rb[OpB::NL];
-    opa.init(tid);
-    opb.init(tid);
+    opa.init(tid, p.g);
+    opb.init(tid, p.g);
     opa.load_edge(ra, tid, S * BK, p.g);
     opb.load_edge(rb, tid, S * BK, p.g);
     __syncthreads();
@@ -979,16 +1027,32 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p) 
   const float* ws = reinterpret_cast<const float*>(p.A) + ((long long)batch * p.k_slices) * p.M * p.N + (long long)m * p.N + n;
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   const bool vec = (p.N % 4 == 0);
-  for (int z = 0; z < p.k_slices; ++z) {
-    const float* src = ws + (long long)z * p.M * p.N;
-    if (vec) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+  const long long slice = (long long)p.M * p.N;
+  // Eight slices are requested together (the loads do not depend on one another; out-of-range slices
+  // re-read the last one) and then added in ascending order, so the result does not depend on the
+  // unrolling while the memory latency is paid once per eight slices instead of once per slice.
+  constexpr int U = 8;
+  for (int z0 = 0; z0 < p.k_slices; z0 += U) {
+    float v[U][4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc[e] += v[e];
-    } else {
+    for (int u = 0; u < U; ++u) {
+      const int z = z0 + u < p.k_slices ? z0 + u : p.k_slices - 1;
+      const float* src = ws + z * slice;
+      if (vec) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(src);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (n + e < p.N) acc[e] += src[e];
+        for (int e = 0; e < 4; ++e) v[u][e] = t[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[u][e] = src[n + e < p.N ? e : 0];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (z0 + u < p.k_slices) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += v[u][e];
+      }
     }
   }
   float col_bias[4] = {0.0f, 0.0f, 0.0f, 0.0f};
