@@ -119,8 +119,8 @@ def side_report(torch, hb, wl, steps=200):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--k", type=int, default=4096)
     ap.add_argument("--config", type=int, default=None, help="force a tile configuration instead of tuning")

@@ -43,6 +43,7 @@ typedef enum {
 typedef enum { HIDET_F32 = 0, HIDET_F16 = 1, HIDET_BF16 = 2 } hidet_dtype_t;
 typedef enum { HIDET_BIAS_NONE = 0, HIDET_BIAS_PER_COL = 1 /* length N */, HIDET_BIAS_PER_ROW = 2 /* length M */ } hidet_bias_axis_t;
 typedef enum { HIDET_ACT_NONE = 0, HIDET_ACT_RELU = 1 } hidet_act_t;
+typedef enum { HIDET_MAP_PLAIN = 0, HIDET_MAP_HEAD_SPLIT = 1 } hidet_out_map_t;
 
 /*
  * Fused epilogue: the elementwise ("bijective") operators that post-scheduling fusion folds into
@@ -54,6 +55,16 @@ typedef enum { HIDET_ACT_NONE = 0, HIDET_ACT_RELU = 1 } hidet_act_t;
  * leading dimension; in batched calls it advances by batch_stride_residual elements per batch
  * entry, while bias is shared by all batch entries.  A NULL epilogue pointer means identity
  * (alpha = 1, nothing else).  struct_size must be sizeof(hidet_epilogue_t).
+ *
+ * out_map rewrites the INDEX of every output store (the other half of what an epilogue may do,
+ * Section 5.2).  HIDET_MAP_PLAIN: C[i][j] at C + i*ldc + j.  HIDET_MAP_HEAD_SPLIT fuses the
+ * reshape + transpose that follows the projection matmuls of a transformer (the
+ * reshape-matmul-transpose sub-graph named in Section 3.2): with i = b*map_seq + s and
+ * j = h*map_head_dim + f, element (i, j) is stored at [b][h][s][f] of a dense tensor
+ * [M/map_seq][N/map_head_dim][map_seq][map_head_dim]; ldc is ignored, residual (if any) is a dense
+ * tensor of that same shape, bias still follows the GEMM index (per column j or per row i).
+ * Only for hidet_gemm* and batch == 1 (HIDET_ERR_UNSUPPORTED otherwise); map_seq must divide M and
+ * map_head_dim must divide N (HIDET_ERR_INVALID_ARG otherwise).
  */
 typedef struct {
   uint32_t struct_size;
@@ -64,6 +75,10 @@ typedef struct {
   const void* residual;
   int64_t ld_residual;
   int64_t batch_stride_residual;
+  int32_t out_map; /* hidet_out_map_t */
+  int32_t reserved; /* must be 0 */
+  int64_t map_seq;
+  int64_t map_head_dim;
 } hidet_epilogue_t;
 
 /*

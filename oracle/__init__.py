@@ -8,6 +8,8 @@ imports it.
   definition of Section 2.3 of the paper; convolution as the definition that img2col + matmul,
   Section 5.2, must reproduce; elementwise epilogue of Section 4.2).  Arithmetic is IEEE double;
   inputs are widened exactly from whatever dtype they arrive in; outputs stay float64.
+* ``head_split`` is the reshape + transpose of the reshape-matmul-transpose sub-graph of Section 3.2,
+  written with numpy's reshape/transpose (an index permutation, no arithmetic).
 * ``oracle.taskmap`` holds the task-mapping definitions of Section 5.1 in pure Python.
 * ``rel_frobenius`` is the error measure used by every parity test.
 """
@@ -200,6 +202,15 @@ def im2col(x, KH, KW, stride=(1, 1), pad=(0, 0)):
     col = np.zeros((IC * KH * KW, Nb * OH * OW), dtype=np.float64)
     load().oracle_im2col(Nb, IC, H, W, KH, KW, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ptr(col))
     return col
+
+
+def head_split(C, seq, head_dim):
+    """[b*seq + s][h*head_dim + f] -> [b][h][s][f]: what a transformer does to the output of its projection
+    matmuls (Section 3.2, reshape-matmul-transpose); the HIP path fuses it into the store."""
+    M, N = C.shape
+    if M % seq or N % head_dim:
+        raise ValueError("seq must divide M and head_dim must divide N")
+    return np.ascontiguousarray(C.reshape(M // seq, seq, N // head_dim, head_dim).transpose(0, 2, 1, 3))
 
 
 def rel_frobenius(got, ref) -> float:

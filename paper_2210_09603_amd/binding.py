@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libhidet_mi355x.so")
 HIDET_F32, HIDET_F16, HIDET_BF16 = 0, 1, 2
 HIDET_BIAS_NONE, HIDET_BIAS_PER_COL, HIDET_BIAS_PER_ROW = 0, 1, 2
 HIDET_ACT_NONE, HIDET_ACT_RELU = 0, 1
+HIDET_MAP_PLAIN, HIDET_MAP_HEAD_SPLIT = 0, 1
 
 _DTYPES = {torch.float32: HIDET_F32, torch.float16: HIDET_F16, torch.bfloat16: HIDET_BF16}
 
@@ -32,6 +33,10 @@ class hidet_epilogue_t(ctypes.Structure):
         ("residual", _vp),
         ("ld_residual", _i64),
         ("batch_stride_residual", _i64),
+        ("out_map", _i32),
+        ("reserved", _i32),
+        ("map_seq", _i64),
+        ("map_head_dim", _i64),
     ]
 
 
@@ -133,9 +138,11 @@ def _ld(t):
     return t.stride(-2) if t.shape[-2] > 1 else max(t.shape[-1], 1)
 
 
-def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None, relu=False, batched=False):
-    """Build a hidet_epilogue_t (returns None for the identity epilogue)."""
-    if alpha == 1.0 and bias is None and residual is None and not relu:
+def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None, relu=False, batched=False,
+                  head_split=None):
+    """Build a hidet_epilogue_t (returns None for the identity epilogue).  head_split=(seq, head_dim) selects the
+    [b][h][s][f] output index map; the residual (if any) is then a dense tensor of that shape."""
+    if alpha == 1.0 and bias is None and residual is None and not relu and head_split is None:
         return None
     e = hidet_epilogue_t()
     e.struct_size = ctypes.sizeof(hidet_epilogue_t)
@@ -143,10 +150,14 @@ def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None
     e.bias = bias.data_ptr() if bias is not None else None
     e.bias_axis = bias_axis if bias is not None else HIDET_BIAS_NONE
     e.act = HIDET_ACT_RELU if relu else HIDET_ACT_NONE
+    if head_split is not None:
+        e.out_map = HIDET_MAP_HEAD_SPLIT
+        e.map_seq, e.map_head_dim = head_split
     if residual is not None:
         e.residual = residual.data_ptr()
-        e.ld_residual = _ld(residual)
-        e.batch_stride_residual = residual.stride(0) if (batched and residual.dim() == 3) else 0
+        if head_split is None:
+            e.ld_residual = _ld(residual)
+            e.batch_stride_residual = residual.stride(0) if (batched and residual.dim() == 3) else 0
     return e
 
 
@@ -165,6 +176,14 @@ def _gemm_dims(A, B, transA, transB):
 def hidet_gemm(A, B, C, transA=False, transB=False, epilogue=None, stream=None, config=-1):
     """C[M,N] = epilogue(op(A) . op(B)); A, B, C are 2-D GPU tensors (row-major, any leading dimension)."""
     M, N, K = _gemm_dims(A, B, transA, transB)
+    if epilogue is not None and epilogue.out_map == HIDET_MAP_HEAD_SPLIT:
+        want = (M // epilogue.map_seq, N // epilogue.map_head_dim, epilogue.map_seq, epilogue.map_head_dim)
+        if tuple(C.shape) != want or not C.is_contiguous():
+            raise ValueError("C must be a dense tensor of shape %s" % (want,))
+        st = lib().hidet_gemm_cfg(config, _dtype(A), _dtype(C), int(transA), int(transB), M, N, K, _ptr(A), _ld(A), _ptr(B),
+                                  _ld(B), _ptr(C), N, _epi_ref(epilogue), _stream(stream))
+        _check(st, "hidet_gemm")
+        return
     if tuple(C.shape) != (M, N):
         raise ValueError("C has shape %s, expected %s" % (tuple(C.shape), (M, N)))
     st = lib().hidet_gemm_cfg(config, _dtype(A), _dtype(C), int(transA), int(transB), M, N, K, _ptr(A), _ld(A), _ptr(B),

@@ -90,6 +90,8 @@ hidet_status_t check_epilogue(const hidet_epilogue_t* epi, int dtype, bool conv)
   if (epi->bias_axis < 0 || epi->bias_axis > 2 || epi->act < 0 || epi->act > 1) return HIDET_ERR_INVALID_ARG;
   if (epi->bias_axis != HIDET_BIAS_NONE && !epi->bias) return HIDET_ERR_INVALID_ARG;
   if (conv && epi->bias_axis == HIDET_BIAS_PER_COL) return HIDET_ERR_INVALID_ARG;
+  if (epi->out_map < 0 || epi->out_map > 1 || epi->reserved != 0) return HIDET_ERR_INVALID_ARG;
+  if (conv && epi->out_map != HIDET_MAP_PLAIN) return HIDET_ERR_INVALID_ARG;
   const size_t es = (size_t)elem_size(dtype);
   if (epi->bias_axis != HIDET_BIAS_NONE && !aligned(epi->bias, es)) return HIDET_ERR_ALIGNMENT;
   if (epi->residual && !aligned(epi->residual, es)) return HIDET_ERR_ALIGNMENT;
@@ -105,6 +107,9 @@ void fill_epilogue(GemmParams& p, const hidet_epilogue_t* epi) {
   p.ldr = 0;
   p.strideR = 0;
   p.relu = 0;
+  p.out_map = 0;
+  p.map_seq = p.map_d = p.map_heads = 1;
+  p.d_seq = p.d_hd = make_fastdiv(1);
   if (epi) {
     p.alpha = epi->alpha;
     p.bias_axis = epi->bias_axis;
@@ -133,7 +138,13 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
     if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return HIDET_ERR_INVALID_ARG;
     if (strideA < 0 || strideB < 0 || strideC < 0) return HIDET_ERR_INVALID_ARG;
     if (batch > 1 && strideC < (M - 1) * ldc + N) return HIDET_ERR_INVALID_ARG;
-    if (epi && epi->residual) {
+    const bool head_split = epi && epi->out_map == HIDET_MAP_HEAD_SPLIT;
+    if (head_split) {
+      if (batch != 1) return HIDET_ERR_UNSUPPORTED;
+      if (epi->map_seq <= 0 || epi->map_head_dim <= 0 || M % epi->map_seq != 0 || N % epi->map_head_dim != 0)
+        return HIDET_ERR_INVALID_ARG;
+    }
+    if (epi && epi->residual && !head_split) {
       if (epi->ld_residual < N) return HIDET_ERR_INVALID_ARG;
       if (epi->batch_stride_residual < 0) return HIDET_ERR_INVALID_ARG;
     }
@@ -168,10 +179,20 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
   const size_t va = 4 * (size_t)elem_size(out);
   bool vs = aligned(C, va) && ldc % 4 == 0 && strideC % 4 == 0;
   if (p.residual) vs = vs && aligned(p.residual, va) && p.ldr % 4 == 0 && p.strideR % 4 == 0;
+  if (!empty && epi && epi->out_map == HIDET_MAP_HEAD_SPLIT) {
+    p.out_map = 1;
+    p.map_seq = (int)epi->map_seq;
+    p.map_d = (int)epi->map_head_dim;
+    p.map_heads = (int)(N / epi->map_head_dim);
+    p.d_seq = make_fastdiv(epi->map_seq);
+    p.d_hd = make_fastdiv(epi->map_head_dim);
+    vs = aligned(C, va) && epi->map_head_dim % 4 == 0 && (!p.residual || aligned(p.residual, va));
+  }
   p.vec_store = vs ? 1 : 0;
   p.out_inner = 1;
   p.out_outer = 0;
   std::memset(&p.g, 0, sizeof(p.g));
+  p.g.d_khw = p.g.d_kw = p.g.d_ohw = p.g.d_ow = make_fastdiv(1);
   return HIDET_OK;
 }
 
@@ -286,7 +307,7 @@ std::vector<float> g_last_times;
 std::string problem_key(const Problem& pr, bool with_workspace = false) {
   char buf[256];
   const GemmParams& p = pr.p;
-  const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0);
+  const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0) | (p.out_map ? 32 : 0);
   if (pr.op == 0)
     std::snprintf(buf, sizeof(buf), "gemm:t%d:%d%d:b%lld:%dx%dx%d:e%d:m%d", pr.dtype, pr.transA, pr.transB, pr.batch, p.M,
                   p.N, p.K, epi_kind, pr.elem_mode);
@@ -370,6 +391,7 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
   q.bias_axis = 0;
   q.residual = nullptr;
   q.relu = 0;
+  q.out_map = 0;
   q.vec_store = (p.N % 4 == 0) ? 1 : 0;
   q.k_slices = (int)actual;
   q.k_slice_len = (int)len;

@@ -97,6 +97,10 @@ struct GemmParams {
   int total_blocks;
   int k_slices;     // > 1: parallel reduction on K -- workgroup z of a tile works on K range [z*k_slice_len, ...)
   int k_slice_len;  // and writes raw fp32 partial sums to slice z of the workspace (C points at the workspace)
+  int out_map;          // MAP_PLAIN kernels: 0 row-major [M][ldc], 1 head split (see head_split_offset)
+  int map_seq, map_d;   // head split: rows per sequence, columns per head
+  int map_heads;        // head split: N / map_d
+  FastDiv d_seq, d_hd;  // dividers by map_seq and map_d
   ConvGeom g;           // img2col geometry (LD_IM2COL) and NCHW map (MAP_NCHW)
   long long out_inner;  // MAP_NCHW: OH*OW
   long long out_outer;  // MAP_NCHW: OC*OH*OW
@@ -523,6 +527,15 @@ __device__ __forceinline__ long long nchw_offset(const GemmParams& p, int m, int
   return (long long)img * p.out_outer + (long long)m * p.out_inner + (n - img * (int)p.out_inner);
 }
 
+// Output index map of the reshape-matmul-transpose sub-graph of transformer models (Section 3.2):
+// GEMM element (m, n) = (sequence b, position s; head h, feature f) with m = b*seq + s, n = h*d + f
+// lives at [b][h][s][f] of a dense tensor.
+__device__ __forceinline__ long long head_split_offset(const GemmParams& p, int m, int n) {
+  const int b = p.d_seq.div(m), s = m - b * p.map_seq;
+  const int h = p.d_hd.div(n), f = n - h * p.map_d;
+  return (((long long)b * p.map_heads + h) * p.map_seq + s) * p.map_d + f;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fused epilogue + predicated store of 4 consecutive output columns of one row.
 // ---------------------------------------------------------------------------------------------
@@ -532,11 +545,19 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
                                        const float (&acc)[4]) {
   if (m >= p.M || n >= p.N) return;
   long long off, roff;
-  if constexpr (MAPPER == MAP_PLAIN) {
+  // the epilogue rewrites the indices of the store as well as its value (Section 5.2)
+  auto mapped = [&](int nn) -> long long {
+    if constexpr (MAPPER == MAP_NCHW)
+      return nchw_offset(p, m, nn);
+    else
+      return head_split_offset(p, m, nn);
+  };
+  const bool remap = (MAPPER == MAP_NCHW) || p.out_map != 0;
+  if (!remap) {
     off = (long long)m * p.ldc + n;
     roff = (long long)m * p.ldr + n;
   } else {
-    off = nchw_offset(p, m, n);
+    off = mapped(n);
     roff = off;
   }
   float v[4];
@@ -565,7 +586,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
       for (int e = 0; e < 4; ++e) {
         if (n + e < p.N) {
           long long ro = roff + e;
-          if constexpr (MAPPER == MAP_NCHW) ro = nchw_offset(p, m, n + e);
+          if (remap) ro = mapped(n + e);
           v[e] += to_f32(R[ro]);
         }
       }
@@ -590,7 +611,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     for (int e = 0; e < 4; ++e) {
       if (n + e < p.N) {
         long long oo = off + e;
-        if constexpr (MAPPER == MAP_NCHW) oo = nchw_offset(p, m, n + e);
+        if (remap) oo = mapped(n + e);
         C[oo] = o[e];
       }
     }

@@ -169,6 +169,57 @@ def test_conv_rectangular_stride_and_padding():
     assert err <= TOL["f16"]
 
 
+def test_case_study_strided_conv_and_larger_batches():
+    # the layer of the schedule-space case study (Section 6.3.1): 28x28, 256 channels, 3x3, padding 1, stride 2
+    c = wl.conv_case(7700, 1, 256, 28, 28, 256, 3, 3, 2, 1, "f16")
+    c.update(relu=True)
+    err, _, ref = run_conv_case(c)
+    _say("case-study conv err %.3e" % err)
+    assert ref.shape == (1, 256, 14, 14) and err <= TOL["f16"]
+    err, _, _ = run_conv_case(c, k_slices=4, config=sliceable_configs("f16")[0])
+    assert err <= TOL["f16"]
+    # batch sizes 4 and 8 (Section 6.3.3) on a bottleneck 3x3 and a 1x1 layer
+    for nb in (4, 8):
+        for (ic, hw, oc, k, s_, p_) in ((64, 28, 64, 3, 1, 1), (128, 14, 256, 1, 1, 0)):
+            c = wl.conv_case(7710 + nb + k, nb, ic, hw, hw, oc, k, k, s_, p_, "f16", residual=True)
+            c.update(relu=True)
+            err, _, _ = run_conv_case(c)
+            _say("batch %d conv k%d err %.3e" % (nb, k, err))
+            assert err <= TOL["f16"]
+
+
+# ------------------------------------------------------------------ output index map (reshape-matmul-transpose)
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_head_split_output_map(dtype):
+    for seed, (b, seq, heads, d), kw in ((7800, (2, 48, 3, 20), dict(bias="col")),       # d % 4 == 0: vector stores
+                                         (7801, (3, 17, 5, 10), dict(residual=True)),    # scalar stores, odd sizes
+                                         (7802, (1, 128, 12, 64), dict(bias="col"))):    # a BERT-base projection
+        M, N, K = b * seq, heads * d, 72 if seed != 7802 else 768
+        c = wl.gemm_case(seed, M, N, K, dtype, **kw)
+        A, B = to_gpu(c["A"], dtype), to_gpu(c["B"], dtype)
+        bias, res = to_gpu(c["bias"], dtype), to_gpu(c["residual"], dtype)
+        if res is not None:  # the residual has the shape of the stored tensor
+            res = res.view(b, seq, heads, d).permute(0, 2, 1, 3).contiguous()
+        ref = oracle.gemm(wl.widen(c["A"], dtype), wl.widen(c["B"], dtype),
+                          bias=None if c["bias"] is None else wl.widen(c["bias"], dtype),
+                          residual=None if c["residual"] is None else wl.widen(c["residual"], dtype), relu=True)
+        ref = oracle.head_split(ref, seq, d)
+        epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, residual=res, relu=True, head_split=(seq, d))
+        for cfg in (-1, applicable_configs(dtype)[-1]):
+            C = torch.full((b, heads, seq, d), float("nan"), dtype=TORCH_DTYPE[dtype], device="cuda")
+            hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg)
+            torch.cuda.synchronize()
+            err = oracle.rel_frobenius(to_f64(C), ref)
+            _say("head split %s %s config %d err %.3e" % (dtype, (b, seq, heads, d), cfg, err))
+            assert err <= TOL[dtype]
+        # the same map applied by the reduce pass of the K-parallel form
+        C = torch.full((b, heads, seq, d), float("nan"), dtype=TORCH_DTYPE[dtype], device="cuda")
+        hb.hidet_batched_gemm_splitk(A, B, C.view(M, N), make_workspace(1, M, N, 2), k_slices=2, epilogue=epi,
+                                     config=sliceable_configs(dtype)[0])
+        torch.cuda.synchronize()
+        assert oracle.rel_frobenius(to_f64(C), ref) <= TOL[dtype]
+
+
 # ------------------------------------------------------------------ degenerate cases and argument checking on the device
 def test_empty_and_k0():
     A = torch.zeros((0, 8), dtype=torch.float16, device="cuda")

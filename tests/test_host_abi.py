@@ -88,6 +88,26 @@ def test_gemm_argument_validation_happens_before_any_launch():
     e.ld_residual = 8
     e.act = 9
     assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    # output index map: head split needs seq | M and head_dim | N, batch 1, a known map id
+    e = hb.hidet_epilogue_t()
+    e.struct_size = ctypes.sizeof(hb.hidet_epilogue_t)
+    e.out_map = hb.HIDET_MAP_HEAD_SPLIT
+    e.map_seq, e.map_head_dim = 3, 4
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID  # 3 does not divide M = 8
+    e.map_seq, e.map_head_dim = 4, 3
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.map_seq, e.map_head_dim = 0, 4
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.map_seq, e.map_head_dim = 4, 4
+    e.out_map = 2
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.out_map = hb.HIDET_MAP_HEAD_SPLIT
+    e.reserved = 1
+    assert _gemm(L, epi=ctypes.byref(e)) == INVALID
+    e.reserved = 0
+    f16 = hb.HIDET_F16
+    assert L.hidet_batched_gemm(f16, f16, 0, 0, 2, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 64, ctypes.byref(e),
+                                None) == UNSUPPORTED
     # empty problems are OK no-ops even with null pointers
     assert _gemm(L, M=0, A=None, B=None, C=None) == 0
     assert _gemm(L, N=0, A=None, B=None, C=None) == 0
@@ -115,6 +135,11 @@ def test_batched_and_conv_argument_validation():
     e.bias = 0x4000
     e.bias_axis = hb.HIDET_BIAS_PER_COL  # conv bias is per output channel = per GEMM row
     assert conv(epi=ctypes.byref(e)) == 1
+    e.bias_axis = hb.HIDET_BIAS_PER_ROW
+    e.out_map = hb.HIDET_MAP_HEAD_SPLIT  # the convolution has its own (NCHW) index map
+    e.map_seq, e.map_head_dim = 1, 1
+    assert conv(epi=ctypes.byref(e)) == 1
+    assert conv(H=40000) == 2 and conv(pw=20000) == 2  # rows/columns are kept in 16-bit fields
     assert hb.lib().hidet_status_string(3) == b"misaligned pointer"
 
 

@@ -241,3 +241,19 @@ def test_fp32_accumulation_bound_is_attainable():
         acc16 = (acc16.astype(np.float32) + p).astype(np.float16)
     assert oracle.rel_frobenius(acc32, ref) < 1e-5
     assert oracle.rel_frobenius(acc16, ref) > 2e-3
+
+
+def test_head_split_is_the_stated_index_permutation():
+    """Brute force over every element of a small case, indices written out by hand."""
+    rng = np.random.default_rng(77)
+    b, seq, heads, d = 2, 5, 3, 4
+    C = rng.standard_normal((b * seq, heads * d))
+    out = oracle.head_split(C, seq, d)
+    assert out.shape == (b, heads, seq, d)
+    for bi in range(b):
+        for h in range(heads):
+            for s_ in range(seq):
+                for f in range(d):
+                    assert out[bi, h, s_, f] == C[bi * seq + s_, h * d + f]
+    with pytest.raises(ValueError):
+        oracle.head_split(C, 4, d)
