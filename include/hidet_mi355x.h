@@ -233,6 +233,26 @@ hidet_status_t hidet_tune_save(const char* path);
 hidet_status_t hidet_tune_load(const char* path);
 
 /*
+ * Reduction template (end of Section 5: next to matrix multiplication, reductions such as a sum along
+ * an axis are the only other hand-written schedule template) and the row softmax built on it, which
+ * turns the two attention products (scores = alpha * Q.K^T, context = S.V) into attention.
+ * x is a row-major [rows][cols] matrix with leading dimension ldx >= cols (elements), DEVICE memory.
+ *
+ * hidet_reduce_rows: y[i] = sum_j x[i][j] (HIDET_REDUCE_SUM), max_j (HIDET_REDUCE_MAX) or the mean
+ *   (HIDET_REDUCE_MEAN); y has `rows` elements of dtype `out`, which is `in` or HIDET_F32
+ *   (HIDET_ERR_UNSUPPORTED otherwise).  Accumulation is fp32.  cols == 0 gives 0, -inf and NaN.
+ * hidet_softmax_rows: y[i][j] = exp(x[i][j] - m_i) / sum_j exp(x[i][j] - m_i) with m_i = max_j x[i][j],
+ *   evaluated in fp32, y of the same dtype and shape with leading dimension ldy >= cols.  y == x
+ *   (with ldy == ldx) is allowed; any other overlap is not.  A row of -inf only yields NaN.
+ * Both: rows == 0 (softmax: or cols == 0) is an OK no-op; asynchronous on `stream`; no allocation.
+ */
+typedef enum { HIDET_REDUCE_SUM = 0, HIDET_REDUCE_MAX = 1, HIDET_REDUCE_MEAN = 2 } hidet_reduce_op_t;
+hidet_status_t hidet_reduce_rows(int32_t in, int32_t out, int32_t op, int64_t rows, int64_t cols, const void* x,
+                                 int64_t ldx, void* y, void* stream);
+hidet_status_t hidet_softmax_rows(int32_t dtype, int64_t rows, int64_t cols, const void* x, int64_t ldx, void* y,
+                                  int64_t ldy, void* stream);
+
+/*
  * Task mappings (Section 5.1): the compile-time mappings the kernels are built from, plus the
  * paper's worked examples, evaluated on the host so that tests can compare them with the
  * definitions.  `expr` receives a string such as "repeat(4,1)*spatial(16,8)".  hidet_taskmap_tasks

@@ -17,6 +17,7 @@ HIDET_F32, HIDET_F16, HIDET_BF16 = 0, 1, 2
 HIDET_BIAS_NONE, HIDET_BIAS_PER_COL, HIDET_BIAS_PER_ROW = 0, 1, 2
 HIDET_ACT_NONE, HIDET_ACT_RELU = 0, 1
 HIDET_MAP_PLAIN, HIDET_MAP_HEAD_SPLIT = 0, 1
+HIDET_REDUCE_SUM, HIDET_REDUCE_MAX, HIDET_REDUCE_MEAN = 0, 1, 2
 
 _DTYPES = {torch.float32: HIDET_F32, torch.float16: HIDET_F16, torch.bfloat16: HIDET_BF16}
 
@@ -57,7 +58,8 @@ EXPORTS = (
     "hidet_tune_last_times", "hidet_tune_clear", "hidet_tune_save", "hidet_tune_load", "hidet_taskmap_count",
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
-    "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk",
+    "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
+    "hidet_softmax_rows",
 )
 
 _lib = None
@@ -92,6 +94,8 @@ def lib():
         tune_tail_sk = [_i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_float)]
         L.hidet_tune_gemm_splitk.argtypes = bgemm_args[:-1] + ws_args + tune_tail_sk
         L.hidet_tune_conv2d_splitk.argtypes = conv_args[:-1] + ws_args + tune_tail_sk
+        L.hidet_reduce_rows.argtypes = [_i32, _i32, _i32, _i64, _i64, _vp, _i64, _vp, _vp]
+        L.hidet_softmax_rows.argtypes = [_i32, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.hidet_tune_last_times.argtypes = [ctypes.POINTER(ctypes.c_float), _i32]
         L.hidet_tune_clear.restype = None
         L.hidet_tune_save.argtypes = [ctypes.c_char_p]
@@ -316,6 +320,37 @@ def hidet_tune_conv2d_splitk(x, w, y, workspace, stride=(1, 1), pad=(0, 0), epil
                                         iters, ctypes.byref(best), ctypes.byref(sl), ctypes.byref(us))
     _check(st, "hidet_tune_conv2d_splitk")
     return best.value, sl.value, us.value
+
+
+def _rows_view(t):
+    """[..., cols] tensor whose leading axes collapse to one row axis with a single stride -> (rows, cols, ld)."""
+    if t.dim() < 1:
+        raise ValueError("need at least one axis")
+    if t.dim() == 1:
+        return 1, t.shape[0], max(t.shape[0], 1)
+    v = t if t.dim() == 2 else (t.view(-1, t.shape[-1]) if t.is_contiguous() else None)
+    if v is None:
+        raise ValueError("leading axes must be collapsible (pass a 2-D view)")
+    return v.shape[0], v.shape[1], _ld(v)
+
+
+def hidet_reduce_rows(x, y, op=HIDET_REDUCE_SUM, stream=None):
+    """y[i] = reduce over the last axis of x; y has one element per row, dtype of x or float32."""
+    rows, cols, ld = _rows_view(x)
+    if y.numel() != rows or not y.is_contiguous():
+        raise ValueError("y must be a dense tensor with one element per row")
+    st = lib().hidet_reduce_rows(_dtype(x), _dtype(y), op, rows, cols, _ptr(x), ld, _ptr(y), _stream(stream))
+    _check(st, "hidet_reduce_rows")
+
+
+def hidet_softmax_rows(x, y, stream=None):
+    """y = softmax of x along the last axis (same shape and dtype; y may be x itself)."""
+    if x.shape != y.shape or x.dtype != y.dtype:
+        raise ValueError("x and y must agree in shape and dtype")
+    rows, cols, ldx = _rows_view(x)
+    _, _, ldy = _rows_view(y)
+    st = lib().hidet_softmax_rows(_dtype(x), rows, cols, _ptr(x), ldx, _ptr(y), ldy, _stream(stream))
+    _check(st, "hidet_softmax_rows")
 
 
 def hidet_tune_last_times():

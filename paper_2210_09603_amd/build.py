@@ -74,7 +74,7 @@ def build(force=False, jobs=None, verbose=True):
             objs.append(obj)
             if not os.path.exists(obj):
                 tasks.append((os.path.join(CSRC, "instances.hip"), obj, ["-DHIDET_TU=%d" % idx, "-DHIDET_TYPE=%d" % t]))
-    for name in ("api", "probe"):
+    for name in ("api", "probe", "reduce"):
         obj = os.path.join(BUILD, name + ".o")
         objs.append(obj)
         if not os.path.exists(obj):

@@ -182,6 +182,21 @@ def test_splitk_argument_validation():
                                     None, 0, None, 3, ctypes.byref(i), ctypes.byref(i), ctypes.byref(f)) == 1
 
 
+def test_reduction_argument_validation():
+    L = hb.lib()
+    f16, f32, bf16 = hb.HIDET_F16, hb.HIDET_F32, hb.HIDET_BF16
+    red = lambda **k: L.hidet_reduce_rows(k.get("i", f16), k.get("o", f16), k.get("op", 0), k.get("rows", 4),
+                                          k.get("cols", 8), k.get("x", 0x1000), k.get("ldx", 8), k.get("y", 0x2000), None)
+    assert red(x=None) == 1 and red(y=None) == 1 and red(ldx=7) == 1 and red(rows=-1) == 1 and red(op=3) == 1
+    assert red(i=5) == 1 and red(o=bf16) == 2 and red(x=0x1001) == 3 and red(o=f32, y=0x2002) == 3
+    assert red(rows=0, x=None, y=None) == 0
+    sm = lambda **k: L.hidet_softmax_rows(k.get("t", f16), k.get("rows", 4), k.get("cols", 8), k.get("x", 0x1000),
+                                          k.get("ldx", 8), k.get("y", 0x2000), k.get("ldy", 8), None)
+    assert sm(x=None) == 1 and sm(y=None) == 1 and sm(ldx=7) == 1 and sm(ldy=7) == 1 and sm(cols=-1) == 1 and sm(t=3) == 1
+    assert sm(y=0x2001) == 3 and sm(cols=2 ** 31) == 2
+    assert sm(rows=0, x=None, y=None) == 0 and sm(cols=0, ldx=0, ldy=0, x=None, y=None) == 0
+
+
 def test_probe_argument_validation():
     L = hb.lib()
     n = L.hidet_probe_scratch_bytes()
