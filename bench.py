@@ -113,7 +113,111 @@ def side_report(torch, hb, wl, steps=200):
     for dt in ("f16", "bf16"):
         for K in (4096, 1024):
             gemm_row(wl.config5(dt, K=K))
+
+    # reduction template: row softmax over the attention scores (memory bound: one read, one write), then the
+    # whole attention chain (scaled Q.K^T, softmax in place, S.V).  Launches are replayed from a HIP graph so that
+    # the Python call overhead stays out of the timing.
+    def graph_time(fn, reps=20, replays=10):
+        fn()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fn()
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(reps):
+                    fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1000.0 / (reps * replays)
+
+    for c in wl.config4("f16"):
+        Q, Kt, V = (dev(c[k], "f16") for k in ("Q", "K", "V"))
+        b, s, d = c["batch"], c["seq"], c["d"]
+        scores = torch.empty((b, s, s), dtype=torch.float16, device="cuda")
+        ctx = torch.empty((b, s, d), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(alpha=c["alpha"])
+        hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi)
+        us = graph_time(lambda: hb.hidet_softmax_rows(scores, scores))
+        nbytes = 2 * scores.numel() * 2
+        rows.append({"workload": c["name"] + "_softmax", "dtype": "f16", "us": round(us, 2), "bound": "hbm",
+                     "algorithmic_GBps": round(nbytes / us * 1e-3, 1), "pct_of_8TBps": round(100 * nbytes / us * 1e-3 / 8000, 2)})
+
+        def chain():
+            hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi)
+            hb.hidet_softmax_rows(scores, scores)
+            hb.hidet_batched_gemm(scores, V, ctx)
+        us = graph_time(chain)
+        flops = 4.0 * b * s * s * d
+        rows.append({"workload": c["name"] + "_attention_3_kernels", "dtype": "f16", "us": round(us, 2),
+                     "TFLOPs": round(flops / us * 1e-6, 2), "pct_peak_mfma": round(100 * flops / us * 1e-6 / PEAK_TFLOPS["f16"], 2)})
     return rows
+
+
+def studies(torch, hb, wl, steps=100):
+    """Schedule-space studies in the manner of Section 6.3.1 (latency of every schedule of the space on one
+    convolution) and Section 6.3.2 (consecutive problem sizes, among them the prime 2039)."""
+    import numpy as np
+
+    def dev(stored):
+        return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+
+    def tile(cfg):
+        i = hb.hidet_config_info(cfg)
+        return "%dx%dx%d/%dx%d/mfma%d/%s" % (i["block_m"], i["block_n"], i["block_k"], i["waves_m"], i["waves_n"], i["mfma"],
+                                            "ring" if i["schedule"] else "2stage")
+
+    out = {}
+    ws = torch.empty(16 << 20, dtype=torch.float32, device="cuda")
+    c = wl.conv_case(6100, 1, 256, 28, 28, 256, 3, 3, 2, 1, "f16")
+    x, w, b = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+    y = torch.empty((1, 256, c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+    sp = dict(stride=(2, 2), pad=(1, 1))
+    t0 = time.perf_counter()
+    best, us = hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp)
+    secs = time.perf_counter() - t0
+    plain = hb.hidet_tune_last_times()
+    best_s, slices, us_s = hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=steps, **sp)
+    sliced = hb.hidet_tune_last_times()
+    out["conv_28x28x256_k3_s2_p1_f16"] = {
+        "best": {"config": best, "tile": tile(best), "us": round(us, 2)},
+        "best_with_k_slices": {"config": best_s, "tile": tile(best_s), "k_slices": slices, "us": round(us_s, 2)},
+        "tuning_seconds_unsliced": round(secs, 3),
+        "schedules": [{"config": i, "tile": tile(i), "us": round(t, 2), "us_best_over_k_slices": round(sliced[i], 2)}
+                      for i, t in enumerate(plain) if t > 0]}
+
+    g = wl.config5("f16")
+    A, B, bias = dev(g["A"]), dev(g["B"]), dev(g["bias"])
+    C = torch.empty((g["M"], g["N"]), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True)
+    t0 = time.perf_counter()
+    best, us = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=20)
+    secs = time.perf_counter() - t0
+    out["gemm_4096_f16"] = {"best": {"config": best, "tile": tile(best), "us": round(us, 2)}, "tuning_seconds": round(secs, 3),
+                            "schedules": [{"config": i, "tile": tile(i), "us": round(t, 2),
+                                           "TFLOPs": round(2.0 * 4096 ** 3 / t * 1e-6, 1)}
+                                          for i, t in enumerate(hb.hidet_tune_last_times()) if t > 0]}
+    del A, B, C
+
+    sweep = []
+    for n in range(2032, 2049):
+        g = wl.gemm_case(6200 + n, n, n, n, "f16", bias="col")
+        A, B, bias = dev(g["A"]), dev(g["B"]), dev(g["bias"])
+        C = torch.empty((n, n), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True)
+        best, us = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=20)
+        sweep.append({"n": n, "config": best, "tile": tile(best), "us": round(us, 2),
+                      "TFLOPs": round(2.0 * n ** 3 / us * 1e-6, 1)})
+    out["gemm_square_sizes_2032_2048_f16"] = sweep
+    return out
 
 
 def main():
@@ -128,13 +232,16 @@ def main():
     ap.add_argument("--report", default=None, metavar="PATH",
                     help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
                          "and write the table to PATH as JSON; the headline line is printed as usual")
+    ap.add_argument("--studies", default=None, metavar="PATH",
+                    help="instead of the benchmark, run the schedule-space studies (latency of every schedule on the "
+                         "case-study convolution and on the headline GEMM; square sizes 2032..2048) and write them to PATH")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 10 plain device-to-device copies of MIB mebibytes "
                          "(known traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by output tiles without any exchange; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path shards by output tiles without any exchange); "
+              "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -145,6 +252,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     hb.lib()  # raises if the HIP extension has not been built
+
+    if args.studies:
+        with open(args.studies, "w") as fh:
+            json.dump(studies(torch, hb, wl), fh, indent=1)
+        print(json.dumps({"studies_written_to": args.studies}))
+        return
 
     if args.copy_calibration > 0:
         n = args.copy_calibration << 20

@@ -179,6 +179,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
   const size_t va = 4 * (size_t)elem_size(out);
   bool vs = aligned(C, va) && ldc % 4 == 0 && strideC % 4 == 0;
   if (p.residual) vs = vs && aligned(p.residual, va) && p.ldr % 4 == 0 && p.strideR % 4 == 0;
+  bool contiguous4 = true;  // row-major: four consecutive columns of a row are always adjacent
   if (!empty && epi && epi->out_map == HIDET_MAP_HEAD_SPLIT) {
     p.out_map = 1;
     p.map_seq = (int)epi->map_seq;
@@ -186,9 +187,10 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
     p.map_heads = (int)(N / epi->map_head_dim);
     p.d_seq = make_fastdiv(epi->map_seq);
     p.d_hd = make_fastdiv(epi->map_head_dim);
-    vs = aligned(C, va) && epi->map_head_dim % 4 == 0 && (!p.residual || aligned(p.residual, va));
+    contiguous4 = epi->map_head_dim % 4 == 0;
+    vs = contiguous4 && aligned(C, va) && (!p.residual || aligned(p.residual, va));
   }
-  p.vec_store = vs ? 1 : 0;
+  p.vec_store = vs ? 2 : (contiguous4 ? 1 : 0);
   p.out_inner = 1;
   p.out_outer = 0;
   std::memset(&p.g, 0, sizeof(p.g));
@@ -249,9 +251,10 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   const int vec = 16 / elem_size(in);
   pr.elem_mode = (aligned(w, 16) && K % vec == 0 && K <= kMaxVecLd) ? 0 : 1;
   const size_t va = 4 * (size_t)elem_size(out);
-  bool vs = aligned(y, va) && p.out_inner % 4 == 0;
+  const bool contiguous4 = p.out_inner % 4 == 0;  // a group of four positions never leaves its image
+  bool vs = aligned(y, va) && contiguous4;
   if (p.residual) vs = vs && aligned(p.residual, va);
-  p.vec_store = vs ? 1 : 0;
+  p.vec_store = vs ? 2 : (contiguous4 ? 1 : 0);
   return HIDET_OK;
 }
 
@@ -392,7 +395,7 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
   q.residual = nullptr;
   q.relu = 0;
   q.out_map = 0;
-  q.vec_store = (p.N % 4 == 0) ? 1 : 0;
+  q.vec_store = (p.N % 4 == 0) ? 2 : 1;
   q.k_slices = (int)actual;
   q.k_slice_len = (int)len;
   q.total_blocks = (int)total;

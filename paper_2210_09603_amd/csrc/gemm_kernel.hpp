@@ -92,7 +92,8 @@ struct GemmParams {
   float alpha;
   int bias_axis;  // 0 none, 1 per column, 2 per row
   int relu;
-  int vec_store;  // 1: groups of 4 consecutive output columns may use one vector access
+  int vec_store;  // groups of 4 consecutive output columns are contiguous in memory and may use one access:
+                  // 0 no, 1 yes at element alignment, 2 yes and every group is aligned to 4 elements
   int tiles_m, tiles_n, group;
   int total_blocks;
   int k_slices;     // > 1: parallel reduction on K -- workgroup z of a tile works on K range [z*k_slice_len, ...)
@@ -322,21 +323,24 @@ struct Operand {
         const T v = src[idx];
         tmp[e] = ok ? v : (T)0.0f;
       }
-    } else if constexpr (LAYOUT == L_KC) {
-      const bool row_ok = sr < rows_left;
-      const long long base = row_ok ? (long long)sr * ld + (k0 + sc) : 0;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        const bool ok = row_ok && (k0 + sc + e < K);
-        const T v = src[ok ? base + e : 0];
-        tmp[e] = ok ? v : (T)0.0f;
-      }
     } else {
-      const bool row_ok = k0 + sr < K;
-      const long long base = row_ok ? (long long)(k0 + sr) * ld + sc : 0;
+      // Element mode: rows are not 16-byte aligned (odd leading dimension, offset pointer).  A chunk that lies
+      // entirely inside the matrix is still fetched with one 16-byte load -- the address is only element
+      // aligned, which global loads accept on this target -- and only chunks that straddle an edge fall back
+      // to one predicated load per element.
+      long long base;
+      int valid;  // elements of the chunk inside the matrix
+      if constexpr (LAYOUT == L_KC) {
+        base = (long long)sr * ld + (k0 + sc);
+        valid = sr < rows_left ? K - (k0 + sc) : 0;
+      } else {
+        base = (long long)(k0 + sr) * ld + sc;
+        valid = k0 + sr < K ? rows_left - sc : 0;
+      }
+      if (valid >= VEC) return reinterpret_cast<const Unaligned*>(src + base)->v;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const bool ok = row_ok && (sc + e < rows_left);
+        const bool ok = e < valid;
         const T v = src[ok ? base + e : 0];
         tmp[e] = ok ? v : (T)0.0f;
       }
@@ -350,6 +354,16 @@ struct Operand {
   // rows or columns that are never stored, so any finite or non-finite value is harmless there.
   // Along K a chunk outside the matrix must read as zero; that can only happen in the last K tile.
   int off[NL];  // element offset of each chunk from `src` at k = 0 (vector mode only)
+  // Element mode: the same idea at element alignment.  eoff = offset of the chunk at k = 0, nv = how many
+  // of its VEC elements lie inside the matrix along M/N (a property of the chunk, not of the K tile).
+  // Chunks entirely outside are redirected to a chunk inside (nv = VEC; they feed outputs that are never
+  // stored); only a chunk that straddles the M/N edge keeps 0 < nv < VEC and is fetched element by element.
+  static constexpr int NE = (MODE == LD_ELEM) ? NL : 1;
+  long long eoff[NE];
+  int nv[NE];
+  struct __attribute__((packed, aligned(sizeof(T)))) Unaligned {
+    u32x4 v;
+  };
   // img2col mode only, per fetched element: offset of input pixel (n, oh*sh - ph, ow*sw - pw) of channel 0
   // from `src` (may be negative), and that pixel's row and column packed as two signed 16-bit fields
   // (row -32768 marks an output position outside the matrix).
@@ -379,6 +393,29 @@ struct Operand {
               ++n;
             }
           }
+        }
+      }
+    }
+    if constexpr (MODE == LD_ELEM) {
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        const int sr = t.i, sc = t.j * VEC;
+        if constexpr (LAYOUT == L_KC) {
+          const int r = sr < rows_left ? sr : rows_left - 1;
+          eoff[q] = (long long)r * ld + sc;
+          nv[q] = VEC;
+        } else {
+          const int rem = rows_left - sc;
+          int c = sc, n = rem;
+          if (rem >= VEC) {
+            n = VEC;
+          } else if (rem <= 0) {
+            n = rows_left >= VEC ? VEC : 0;  // a matrix narrower than one chunk has nowhere to redirect to
+            c = rows_left >= VEC ? rows_left - VEC : 0;
+          }
+          eoff[q] = (long long)sr * ld + c;
+          nv[q] = n;
         }
       }
     }
@@ -437,6 +474,23 @@ struct Operand {
       const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
 #pragma unroll
       for (int q = 0; q < NL; ++q) regs[q] = *reinterpret_cast<const u32x4*>(base + off[q]);
+    } else if constexpr (MODE == LD_ELEM) {
+      const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        if (nv[q] == VEC) {
+          regs[q] = reinterpret_cast<const Unaligned*>(base + eoff[q])->v;
+        } else {
+          T tmp[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const bool ok = e < nv[q];
+            const T v = base[ok ? eoff[q] + e : eoff[q]];
+            tmp[e] = ok ? v : (T)0.0f;
+          }
+          regs[q] = __builtin_bit_cast(u32x4, tmp);
+        }
+      }
     } else {
       load_edge(regs, tid, k0, g);
     }
@@ -560,6 +614,10 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     off = mapped(n);
     roff = off;
   }
+  // four consecutive elements as one access; the address need only be element aligned
+  struct __attribute__((packed, aligned(sizeof(TO)))) Quad {
+    TO e[4];
+  };
   float v[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) v[e] = p.alpha * acc[e];
@@ -575,10 +633,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
   if (R != nullptr) {
     if (whole) {
       TO r[4];
-      if constexpr (sizeof(TO) == 2)
-        *reinterpret_cast<u32x2*>(r) = *reinterpret_cast<const u32x2*>(R + roff);
-      else
-        *reinterpret_cast<u32x4*>(r) = *reinterpret_cast<const u32x4*>(R + roff);
+      *reinterpret_cast<Quad*>(r) = *reinterpret_cast<const Quad*>(R + roff);
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] += to_f32(r[e]);
     } else {
@@ -602,10 +657,14 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
   if (whole) {
     // streaming stores: the output is not read again by this kernel, and lines that do not linger
     // dirty in L2 shorten the write-back at the end of the kernel
-    if constexpr (sizeof(TO) == 2)
-      __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(o), reinterpret_cast<u32x2*>(C + off));
-    else
-      __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(o), reinterpret_cast<u32x4*>(C + off));
+    if (p.vec_store == 2) {  // 4-element aligned address
+      if constexpr (sizeof(TO) == 2)
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(o), reinterpret_cast<u32x2*>(C + off));
+      else
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(o), reinterpret_cast<u32x4*>(C + off));
+    } else {
+      *reinterpret_cast<Quad*>(C + off) = *reinterpret_cast<const Quad*>(o);
+    }
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {

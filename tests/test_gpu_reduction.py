@@ -130,3 +130,39 @@ def test_attention_from_the_three_calls(batch, seq):
     err = oracle.rel_frobenius(to_f64(ctx), ref)
     _say("attention b%d s%d err %.3e" % (batch, seq, err))
     assert err <= TOL["f16"]
+
+
+def test_hip_graph_replays_of_the_attention_chain_match_eager():
+    """The library only launches kernels on the caller's stream (no allocation, no memset, no synchronisation),
+    so a caller may capture it; every replay must reproduce the eager result bit for bit."""
+    c = wl.attention_case(9500, 6, 128, "f16")
+    Q, K, V = (to_gpu(c[k], "f16") for k in ("Q", "K", "V"))
+    scores = torch.empty((6, 128, 128), dtype=torch.float16, device="cuda")
+    ctx = torch.zeros((6, 128, 64), dtype=torch.float16, device="cuda")
+    epi = hb.make_epilogue(alpha=c["alpha"])
+
+    def chain():
+        hb.hidet_batched_gemm(Q, K, scores, transB=True, epilogue=epi)
+        hb.hidet_softmax_rows(scores, scores)
+        hb.hidet_batched_gemm(scores, V, ctx)
+
+    chain()
+    torch.cuda.synchronize()
+    eager = ctx.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        chain()  # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            chain()
+    for replay in range(3):
+        ctx.zero_()
+        scores.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ctx, eager), replay
+        V2 = V * 1.0  # unrelated eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(V2, V)
