@@ -22,7 +22,7 @@ PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}  # 256 CUs x 4 SIMDs
 
 # HBM bytes per launch of the dominant kernel at 4096^3, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
 # scaled by a plain copy of known size (profiles/gemm_pingpong_f16_4096.md); None for workloads not measured.
-MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235323351}
+MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235985819}
 
 
 def side_report(torch, hb, wl, steps=200):
@@ -161,6 +161,58 @@ def side_report(torch, hb, wl, steps=200):
     return rows
 
 
+def other_workload(torch, hb, wl, which, steps, warmup):
+    """One of the secondary kernels on its own, K steps after W warm-up steps, so that a profiler sees nothing else:
+    "softmax" = row softmax over the scores of the largest attention case (memory bound), "conv" = the case-study
+    convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced)."""
+    import numpy as np
+
+    def dev(stored):
+        return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+
+    if which == "softmax":
+        b, s = 192, 512
+        g = wl.rng(6300)
+        x = dev(wl.to_storage(g.standard_normal((b * s, s)).astype(np.float32), "f16"))
+        y = torch.empty_like(x)
+        step = lambda: hb.hidet_softmax_rows(x, y)
+        name = "row softmax, f16, %d rows x %d columns (scores of attention batch*heads=192, seq=512), N(0,1)" % (b * s, s)
+        unit_bytes = 2 * x.numel() * 2
+        extra = {}
+    else:
+        c = wl.conv_case(6100, 1, 256, 28, 28, 256, 3, 3, 2, 1, "f16")
+        x, w, bias = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+        y = torch.empty((1, 256, c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+        ws = torch.empty(16 << 20, dtype=torch.float32, device="cuda")
+        epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+        sp = dict(stride=(2, 2), pad=(1, 1))
+        cfg, slices, _ = hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=50, **sp)
+        step = lambda: hb.hidet_conv2d_implicit_gemm_splitk(x, w, y, ws, k_slices=slices, config=cfg, epilogue=epi, **sp)
+        name = "conv2d 1x256x28x28 -> 256, 3x3, stride 2, pad 1, f16, bias + ReLU, He-init weights, seed 6100"
+        unit_bytes = (x.numel() + w.numel() + y.numel() + bias.numel()) * 2
+        extra = {"tile_config": cfg, "k_slices": slices,
+                 "flops": 2.0 * 256 * c["OH"] * c["OW"] * 256 * 9}
+    for _ in range(warmup):
+        step()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbps = unit_bytes / (ms * 1e-3) / 1e9
+    out = {"metric": "algorithmic GB/s of one secondary kernel, 1 GPU", "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 6), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f16", "data": "synthetic", "config": dict(workload=name, **extra),
+           "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s",
+                        "frac": round(gbps / 8000.0, 4), "traffic": None}}
+    if "flops" in extra:
+        out["config"]["TFLOPs"] = round(extra["flops"] / (ms * 1e-3) / 1e12, 2)
+    return out
+
+
 def studies(torch, hb, wl, steps=100):
     """Schedule-space studies in the manner of Section 6.3.1 (latency of every schedule of the space on one
     convolution) and Section 6.3.2 (consecutive problem sizes, among them the prime 2039)."""
@@ -232,6 +284,8 @@ def main():
     ap.add_argument("--report", default=None, metavar="PATH",
                     help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
                          "and write the table to PATH as JSON; the headline line is printed as usual")
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv"],
+                    help="gemm (default): the headline benchmark; softmax / conv: one secondary kernel alone (for profiling)")
     ap.add_argument("--studies", default=None, metavar="PATH",
                     help="instead of the benchmark, run the schedule-space studies (latency of every schedule on the "
                          "case-study convolution and on the headline GEMM; square sizes 2032..2048) and write them to PATH")
@@ -257,6 +311,10 @@ def main():
         with open(args.studies, "w") as fh:
             json.dump(studies(torch, hb, wl), fh, indent=1)
         print(json.dumps({"studies_written_to": args.studies}))
+        return
+
+    if args.workload != "gemm":
+        print(json.dumps(other_workload(torch, hb, wl, args.workload, args.steps, args.warmup)))
         return
 
     if args.copy_calibration > 0:

@@ -260,7 +260,10 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
 
 LaunchFn find_launcher(const Problem& pr, int config) {
   if (config < 0 || config >= kNumConfigs) return nullptr;
-  const int variant = pr.op == 1 ? conv_variant(pr.elem_mode) : gemm_variant(pr.transA, pr.transB, pr.elem_mode);
+  // The ring schedule is built without the run-time output map; a head-split problem takes the same tile's
+  // general-schedule kernel (the element-mode variant, which is as fast as vector mode on aligned operands).
+  const int elem = (pr.p.out_map != 0 && kConfigs[config].sched == 1) ? 1 : pr.elem_mode;
+  const int variant = pr.op == 1 ? conv_variant(elem) : gemm_variant(pr.transA, pr.transB, elem);
   return registry().fn[config][pr.dtype][variant];
 }
 

@@ -98,7 +98,7 @@ struct GemmParams {
   int total_blocks;
   int k_slices;     // > 1: parallel reduction on K -- workgroup z of a tile works on K range [z*k_slice_len, ...)
   int k_slice_len;  // and writes raw fp32 partial sums to slice z of the workspace (C points at the workspace)
-  int out_map;          // MAP_PLAIN kernels: 0 row-major [M][ldc], 1 head split (see head_split_offset)
+  int out_map;          // MAP_PLAIN kernels: 0 row-major [M][ldc], 1 head split (see row_offset / col_offset)
   int map_seq, map_d;   // head split: rows per sequence, columns per head
   int map_heads;        // head split: N / map_d
   FastDiv d_seq, d_hd;  // dividers by map_seq and map_d
@@ -574,46 +574,55 @@ struct Operand {
   }
 };
 
-// Output index map of the convolution: GEMM element (m, n) = (output channel, image * OH*OW + pixel)
-// lives at [image][m][pixel] of the NCHW tensor.
-__device__ __forceinline__ long long nchw_offset(const GemmParams& p, int m, int n) {
-  const int img = p.g.d_ohw.div(n);
-  return (long long)img * p.out_outer + (long long)m * p.out_inner + (n - img * (int)p.out_inner);
+// Output index maps (the index half of an epilogue, Section 5.2).  All of them are separable,
+//     offset(m, n) = row_offset(m) + col_offset(n),
+// so a lane that keeps its columns computes the column part once and the row part once per row:
+//   plain        m * ldc                    + n
+//   NCHW (conv)  m * OH*OW                  + image * OC*OH*OW + pixel          (n = image * OH*OW + pixel)
+//   head split   ((b * heads) * seq + s) * d + h * seq * d + f                  (m = b*seq + s, n = h*d + f;
+//                the reshape-matmul-transpose sub-graph of transformer models, Section 3.2)
+// DYN = false compiles the run-time choice between plain and head split out of MAP_PLAIN kernels (the
+// large-tile schedule is built that way: its register budget is tight enough that the extra live values
+// cost several percent of its main loop).
+template <int MAPPER, bool DYN = true>
+__device__ __forceinline__ long long col_offset(const GemmParams& p, int n) {
+  if constexpr (MAPPER == MAP_NCHW) {
+    const int img = p.g.d_ohw.div(n);
+    return (long long)img * p.out_outer + (n - img * (int)p.out_inner);
+  } else {
+    if (DYN && p.out_map != 0) {
+      const int h = p.d_hd.div(n);
+      return (long long)h * p.map_seq * p.map_d + (n - h * p.map_d);
+    }
+    return n;
+  }
 }
-
-// Output index map of the reshape-matmul-transpose sub-graph of transformer models (Section 3.2):
-// GEMM element (m, n) = (sequence b, position s; head h, feature f) with m = b*seq + s, n = h*d + f
-// lives at [b][h][s][f] of a dense tensor.
-__device__ __forceinline__ long long head_split_offset(const GemmParams& p, int m, int n) {
-  const int b = p.d_seq.div(m), s = m - b * p.map_seq;
-  const int h = p.d_hd.div(n), f = n - h * p.map_d;
-  return (((long long)b * p.map_heads + h) * p.map_seq + s) * p.map_d + f;
+template <int MAPPER, bool DYN = true>
+__device__ __forceinline__ long long row_offset(const GemmParams& p, int m, long long ld) {
+  if constexpr (MAPPER == MAP_NCHW) {
+    return (long long)m * p.out_inner;
+  } else {
+    if (DYN && p.out_map != 0) {
+      const int b = p.d_seq.div(m), s = m - b * p.map_seq;
+      return ((long long)b * p.map_heads * p.map_seq + s) * p.map_d;
+    }
+    return (long long)m * ld;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fused epilogue + predicated store of 4 consecutive output columns of one row.
+// Fused epilogue + predicated store of 4 consecutive output columns of one row.  `ccol` is
+// col_offset(n), computed by the caller once for all its rows.
 // ---------------------------------------------------------------------------------------------
-template <typename TO, int MAPPER>
+template <typename TO, int MAPPER, bool DYN = true>
 __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, const TO* __restrict__ R,
                                        const TO* __restrict__ bias, const float (&col_bias)[4], int m, int n,
-                                       const float (&acc)[4]) {
+                                       long long ccol, const float (&acc)[4]) {
   if (m >= p.M || n >= p.N) return;
-  long long off, roff;
-  // the epilogue rewrites the indices of the store as well as its value (Section 5.2)
-  auto mapped = [&](int nn) -> long long {
-    if constexpr (MAPPER == MAP_NCHW)
-      return nchw_offset(p, m, nn);
-    else
-      return head_split_offset(p, m, nn);
-  };
-  const bool remap = (MAPPER == MAP_NCHW) || p.out_map != 0;
-  if (!remap) {
-    off = (long long)m * p.ldc + n;
-    roff = (long long)m * p.ldr + n;
-  } else {
-    off = mapped(n);
-    roff = off;
-  }
+  const bool remap = (MAPPER == MAP_NCHW) || (DYN && p.out_map != 0);
+  const long long crow = row_offset<MAPPER, DYN>(p, m, p.ldc);
+  const long long rrow = remap ? crow : (long long)m * p.ldr;
+  const long long off = crow + ccol, roff = rrow + ccol;
   // four consecutive elements as one access; the address need only be element aligned
   struct __attribute__((packed, aligned(sizeof(TO)))) Quad {
     TO e[4];
@@ -641,7 +650,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
       for (int e = 0; e < 4; ++e) {
         if (n + e < p.N) {
           long long ro = roff + e;
-          if (remap) ro = mapped(n + e);
+          if (remap) ro = rrow + col_offset<MAPPER, DYN>(p, n + e);
           v[e] += to_f32(R[ro]);
         }
       }
@@ -670,7 +679,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     for (int e = 0; e < 4; ++e) {
       if (n + e < p.N) {
         long long oo = off + e;
-        if (remap) oo = mapped(n + e);
+        if (remap) oo = crow + col_offset<MAPPER, DYN>(p, n + e);
         C[oo] = o[e];
       }
     }
@@ -763,7 +772,7 @@ __device__ __forceinline__ void load_col_bias(const GemmParams& p, int n_wave0, 
 // as whole 128-byte lines.  No workgroup barrier is involved: the region is private to the wave and
 // a wave's LDS operations complete in order (the fences are wave-scope, LDS-only).
 // Must be entered after a workgroup barrier that ends all use of the staging buffers.
-template <class Cfg, class Acc>
+template <class Cfg, class Acc, bool DYN = true>
 __device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords& bc, int wave, int lane, int wm0, int wn0,
                                          Acc (&acc)[Cfg::FM][Cfg::FN], const float (&col_bias)[4], unsigned char* smem) {
   using TO = typename Cfg::TO;
@@ -778,6 +787,8 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords&
   constexpr int READS = (SLOTS + 63) / 64;
   static_assert(64 % LANES_PER_ROW == 0, "a lane must keep the same 4 columns in every read-back step");
   unsigned char* region = smem + wave * (MI * ROW_BYTES);
+  const int my_n = bc.n0 + wn0 + (lane % LANES_PER_ROW) * 4;  // the same 4 columns in every read-back step
+  const long long my_ccol = col_offset<Cfg::MAPPER, DYN>(p, my_n);
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
 #pragma unroll
@@ -798,7 +809,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords&
       if (SLOTS % 64 == 0 || idx < SLOTS) {
         const f32x4 v = *reinterpret_cast<const f32x4*>(region + row * ROW_BYTES + c4 * 16);
         const float vv[4] = {v[0], v[1], v[2], v[3]};
-        store4<TO, Cfg::MAPPER>(p, C, R, bias, col_bias, bc.m0 + wm0 + i * MI + row, bc.n0 + wn0 + c4 * 4, vv);
+        store4<TO, Cfg::MAPPER, DYN>(p, C, R, bias, col_bias, bc.m0 + wm0 + i * MI + row, my_n, my_ccol, vv);
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
@@ -1086,7 +1097,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
   }
   __syncthreads();  // the epilogue reuses the LDS
 
-  epilogue<Cfg>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
+  epilogue<Cfg, Acc, false>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1144,7 +1155,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p) 
   }
   TO* C = reinterpret_cast<TO*>(p.C) + (long long)batch * p.strideC;
   const TO* R = p.residual ? reinterpret_cast<const TO*>(p.residual) + (long long)batch * p.strideR : nullptr;
-  store4<TO, MAPPER>(p, C, R, bias, col_bias, m, n, acc);
+  store4<TO, MAPPER>(p, C, R, bias, col_bias, m, n, col_offset<MAPPER>(p, n), acc);
 }
 
 }  // namespace hidet
