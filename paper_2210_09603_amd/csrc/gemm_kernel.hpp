@@ -330,14 +330,35 @@ struct Operand {
       // to one predicated load per element.
       long long base;
       int valid;  // elements of the chunk inside the matrix
+      bool whole;  // the 16 bytes of the chunk may be read at once
       if constexpr (LAYOUT == L_KC) {
         base = (long long)sr * ld + (k0 + sc);
         valid = sr < rows_left ? K - (k0 + sc) : 0;
+        // a chunk that sticks out along K is read whole and masked below, unless it ends the last row
+        whole = valid >= VEC || (valid > 0 && (kofs + k0 + sc + VEC <= ld || sr < rows_left - 1));
       } else {
         base = (long long)(k0 + sr) * ld + sc;
         valid = k0 + sr < K ? rows_left - sc : 0;
+        // a chunk that sticks out along M/N may be read whole (see init) unless it ends the last row
+        whole = valid >= VEC || (valid > 0 && (r0 + sc + VEC <= ld || k0 + sr < K - 1));
       }
-      if (valid >= VEC) return reinterpret_cast<const Unaligned*>(src + base)->v;
+      if (valid <= 0) return u32x4{0u, 0u, 0u, 0u};
+      if (whole) {
+        u32x4 v = reinterpret_cast<const Unaligned*>(src + base)->v;
+        if constexpr (LAYOUT == L_KC) {
+          // along K what lies beyond the matrix must contribute exact zeros
+          if (valid < VEC) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if constexpr (IS_F32)
+                v[i] = valid > i ? v[i] : 0u;
+              else
+                v[i] &= valid >= 2 * i + 2 ? 0xffffffffu : (valid == 2 * i + 1 ? 0x0000ffffu : 0u);
+            }
+          }
+        }
+        return v;
+      }
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         const bool ok = e < valid;
@@ -357,7 +378,11 @@ struct Operand {
   // Element mode: the same idea at element alignment.  eoff = offset of the chunk at k = 0, nv = how many
   // of its VEC elements lie inside the matrix along M/N (a property of the chunk, not of the K tile).
   // Chunks entirely outside are redirected to a chunk inside (nv = VEC; they feed outputs that are never
-  // stored); only a chunk that straddles the M/N edge keeps 0 < nv < VEC and is fetched element by element.
+  // stored).  A chunk that straddles the M/N edge is still read whole: the bytes past the edge are the
+  // padding of the row or the beginning of the next row -- valid memory, and values that only reach
+  // outputs that are never stored.  The exception is the last row of the operand, where "past the edge"
+  // may be past the allocation: nv = -(valid elements) marks such chunks, and the one row concerned is
+  // fetched element by element (so is everything in a matrix narrower than one chunk, 0 <= nv < VEC).
   static constexpr int NE = (MODE == LD_ELEM) ? NL : 1;
   long long eoff[NE];
   int nv[NE];
@@ -410,7 +435,9 @@ struct Operand {
           int c = sc, n = rem;
           if (rem >= VEC) {
             n = VEC;
-          } else if (rem <= 0) {
+          } else if (rem > 0) {
+            n = (r0 + sc + VEC <= ld) ? VEC : -rem;  // the padding of the row covers the over-read
+          } else {
             n = rows_left >= VEC ? VEC : 0;  // a matrix narrower than one chunk has nowhere to redirect to
             c = rows_left >= VEC ? rows_left - VEC : 0;
           }
@@ -478,13 +505,15 @@ struct Operand {
       const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
 #pragma unroll
       for (int q = 0; q < NL; ++q) {
-        if (nv[q] == VEC) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        if (nv[q] == VEC || (nv[q] < 0 && k0 + t.i < K - 1)) {
           regs[q] = reinterpret_cast<const Unaligned*>(base + eoff[q])->v;
         } else {
+          const int cnt = nv[q] < 0 ? -nv[q] : nv[q];
           T tmp[VEC];
 #pragma unroll
           for (int e = 0; e < VEC; ++e) {
-            const bool ok = e < nv[q];
+            const bool ok = e < cnt;
             const T v = base[ok ? eoff[q] + e : eoff[q]];
             tmp[e] = ok ? v : (T)0.0f;
           }
