@@ -269,6 +269,21 @@ def studies(torch, hb, wl, steps=100):
         sweep.append({"n": n, "config": best, "tile": tile(best), "us": round(us, 2),
                       "TFLOPs": round(2.0 * n ** 3 / us * 1e-6, 1)})
     out["gemm_square_sizes_2032_2048_f16"] = sweep
+
+    # batch sizes 1, 4, 8 on the four bottleneck convolutions (after Section 6.3.3)
+    batches = []
+    for i, (IC, H, W, OC, KH, KW, s_, p_) in enumerate(wl.RESNET50_CONVS):
+        for nb in (1, 4, 8):
+            c = wl.conv_case(6400 + 10 * i + nb, nb, IC, H, W, OC, KH, KW, s_, p_, "f16")
+            x, w, b = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+            y = torch.empty((nb, OC, c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+            epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+            sp = dict(stride=(s_, s_), pad=(p_, p_))
+            best, slices, us = hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=steps, **sp)
+            flops = 2.0 * nb * OC * c["OH"] * c["OW"] * IC * KH * KW
+            batches.append({"layer": "%dx%d %d->%d k%d" % (H, W, IC, OC, KH), "batch": nb, "config": best, "tile": tile(best),
+                            "k_slices": slices, "us": round(us, 2), "TFLOPs": round(flops / us * 1e-6, 2)})
+    out["conv_batch_1_4_8_f16"] = batches
     return out
 
 

@@ -59,7 +59,7 @@ EXPORTS = (
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
-    "hidet_softmax_rows",
+    "hidet_softmax_rows", "hidet_host_div",
 )
 
 _lib = None
@@ -94,6 +94,7 @@ def lib():
         tune_tail_sk = [_i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_float)]
         L.hidet_tune_gemm_splitk.argtypes = bgemm_args[:-1] + ws_args + tune_tail_sk
         L.hidet_tune_conv2d_splitk.argtypes = conv_args[:-1] + ws_args + tune_tail_sk
+        L.hidet_host_div.argtypes = [_i64, _i32, ctypes.POINTER(_i32)]
         L.hidet_reduce_rows.argtypes = [_i32, _i32, _i32, _i64, _i64, _vp, _i64, _vp, _vp]
         L.hidet_softmax_rows.argtypes = [_i32, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.hidet_tune_last_times.argtypes = [ctypes.POINTER(ctypes.c_float), _i32]

@@ -758,6 +758,12 @@ hidet_status_t hidet_block_task(int32_t tiles_m, int32_t tiles_n, int32_t group,
   return HIDET_OK;
 }
 
+hidet_status_t hidet_host_div(int64_t divisor, int32_t n, int32_t* quotient) {
+  if (divisor <= 0 || divisor > kIntMax || n < 0 || !quotient) return HIDET_ERR_INVALID_ARG;
+  *quotient = make_fastdiv(divisor).div(n);
+  return HIDET_OK;
+}
+
 const char* hidet_status_string(int32_t status) {
   switch (status) {
     case HIDET_OK: return "ok";

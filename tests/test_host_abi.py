@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from oracle import taskmap as otm
@@ -180,6 +181,32 @@ def test_splitk_argument_validation():
     i = ctypes.c_int32()
     assert L.hidet_tune_gemm_splitk(f16, f16, 0, 0, 1, 64, 64, 1024, 0x1000, 1024, 0, 0x2000, 64, 0, 0x3000, 64, 0, None,
                                     None, 0, None, 3, ctypes.byref(i), ctypes.byref(i), ctypes.byref(f)) == 1
+
+
+def test_multiply_shift_division_equals_floor_division():
+    """The divider the kernels use for index arithmetic, checked where such schemes go wrong: every n for small
+    divisors, and the neighbourhood of every multiple near the top of the 31-bit range for a spread of divisors."""
+    L = hb.lib()
+    q = ctypes.c_int32()
+
+    def div(d, n):
+        assert L.hidet_host_div(d, n, ctypes.byref(q)) == 0
+        return q.value
+    for d in range(1, 40):
+        for n in range(0, 2000):
+            assert div(d, n) == n // d, (d, n)
+    rng = np.random.default_rng(123)
+    top = 2 ** 31 - 1
+    divisors = [1, 2, 3, 7, 9, 49, 196, 3136, 12544, 2 ** 16 - 1, 2 ** 16, 2 ** 16 + 1, 2 ** 30, 2 ** 30 + 1, top - 1, top]
+    divisors += [int(x) for x in rng.integers(1, top, size=60)]
+    for d in divisors:
+        probes = {0, 1, d - 1, d, d + 1, top, top - 1, (top // d) * d, (top // d) * d - 1, max((top // d) * d - d, 0)}
+        probes |= {int(x) for x in rng.integers(0, top, size=50)}
+        for n in probes:
+            if 0 <= n <= top:
+                assert div(d, n) == n // d, (d, n)
+    assert L.hidet_host_div(0, 5, ctypes.byref(q)) == 1 and L.hidet_host_div(3, -1, ctypes.byref(q)) == 1
+    assert L.hidet_host_div(3, 5, None) == 1
 
 
 def test_reduction_argument_validation():
