@@ -107,7 +107,8 @@ hidet_status_t hidet_batched_gemm(int32_t in, int32_t out, int32_t transA, int32
  * y = epilogue( conv2d(x, w) ): NCHW input x[Nb][IC][H][W], OIHW weights w[OC][IC][KH][KW], NCHW
  * output y[Nb][OC][OH][OW], OH = floor((H + 2*pad_h - KH)/stride_h) + 1 (same for OW), all three
  * tensors dense.  Cross-correlation with zero padding, dilation 1, groups 1.  Computed as an
- * implicit GEMM (Sections 5.2 and 6.3.4): GEMM M = OC, GEMM N = Nb*OH*OW, GEMM K = IC*KH*KW; the
+ * implicit GEMM (Sections 5.2 and 6.3.4): GEMM M = OC, GEMM N = Nb*OH*OW (internally Nb*OH*roundup(OW, 8):
+ * output rows are padded so that 8 consecutive columns are 8 consecutive pixels), GEMM K = IC*KH*KW; the
  * img2col gather is the fused prologue of the B operand and the NCHW index map is part of the
  * fused epilogue, so no img2col matrix is ever materialised.  In the epilogue, bias (if any) must
  * be HIDET_BIAS_PER_ROW, i.e. one value per output channel, and residual (if any) is a dense
@@ -183,7 +184,8 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
  *
  *   workspace        DEVICE pointer, 16-byte aligned, caller-owned, at least
  *                    hidet_splitk_workspace_bytes(batch, M, N, k_slices) bytes (for the convolution:
- *                    batch = 1, M = OC, N = Nb*OH*OW); contents on entry ignored, clobbered on return;
+ *                    batch = 1, M = OC, N = Nb*OH*roundup(OW, 8): the implicit GEMM pads every output
+ *                    row to a multiple of 8 columns); contents on entry ignored, clobbered on return;
  *                    layout [batch][slice][M][N] fp32.  Calls that share a workspace must be ordered
  *                    on one stream.
  *   k_slices         > 1: requested slice count (the effective count may be smaller when K has fewer

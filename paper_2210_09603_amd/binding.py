@@ -264,6 +264,12 @@ def hidet_splitk_workspace_bytes(batch, M, N, k_slices):
     return lib().hidet_splitk_workspace_bytes(batch, M, N, k_slices)
 
 
+def conv_gemm_n(y_shape):
+    """GEMM N of the implicit-GEMM convolution that produces y [Nb, OC, OH, OW]: output rows padded to 8 columns."""
+    Nb, _, OH, OW = y_shape
+    return Nb * OH * ((OW + 7) // 8 * 8)
+
+
 def _ws(workspace):
     """(pointer, bytes) of a workspace tensor (any dtype, contiguous) or (NULL, 0)."""
     if workspace is None:

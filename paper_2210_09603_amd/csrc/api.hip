@@ -194,7 +194,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
   p.out_inner = 1;
   p.out_outer = 0;
   std::memset(&p.g, 0, sizeof(p.g));
-  p.g.d_khw = p.g.d_kw = p.g.d_ohw = p.g.d_ow = make_fastdiv(1);
+  p.g.d_khw = p.g.d_kw = p.g.d_owp = p.g.d_oh = make_fastdiv(1);
   return HIDET_OK;
 }
 
@@ -209,7 +209,9 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   if (st != HIDET_OK) return st;
   const long long OH = (H + 2 * ph - KH) >= 0 ? (H + 2 * ph - KH) / sh + 1 : 0;
   const long long OW = (W + 2 * pw - KW) >= 0 ? (W + 2 * pw - KW) / sw + 1 : 0;
-  const long long M = OC, N = Nb * OH * OW, K = IC * KH * KW;
+  // GEMM columns enumerate output positions with every output row padded to a multiple of 8 (see ConvGeom)
+  const long long OWP = (OW + 7) / 8 * 8;
+  const long long M = OC, N = Nb * OH * OWP, K = IC * KH * KW;
   // the gather keeps input rows and columns (padding included) in signed 16-bit fields and element
   // offsets in 32 bits
   if (M > kIntMax || N > kIntMax || K > kIntMax || Nb * IC * H * W > kIntMax || H + 2 * ph > 32767 ||
@@ -244,17 +246,18 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   p.ldr = 0;
   p.strideR = 0;
   p.g = ConvGeom{(int)IC, (int)H, (int)W, (int)KH, (int)KW, (int)sh, (int)sw, (int)ph, (int)pw, (int)OH, (int)OW,
-                 make_fastdiv(KH * KW), make_fastdiv(KW), make_fastdiv(OH * OW > 0 ? OH * OW : 1),
-                 make_fastdiv(OW > 0 ? OW : 1)};
+                 (int)OWP, (int)(Nb * IC * H * W), make_fastdiv(KH * KW), make_fastdiv(KW),
+                 make_fastdiv(OWP > 0 ? OWP : 1), make_fastdiv(OH > 0 ? OH : 1)};
   p.out_inner = OH * OW;
   p.out_outer = OC * OH * OW;
   const int vec = 16 / elem_size(in);
   pr.elem_mode = (aligned(w, 16) && K % vec == 0 && K <= kMaxVecLd) ? 0 : 1;
   const size_t va = 4 * (size_t)elem_size(out);
-  const bool contiguous4 = p.out_inner % 4 == 0;  // a group of four positions never leaves its image
-  bool vs = aligned(y, va) && contiguous4;
+  // a group of four positions never leaves its (padded) output row, so it is always contiguous in y;
+  // it is aligned to four elements when every output row is
+  bool vs = aligned(y, va) && OW % 4 == 0;
   if (p.residual) vs = vs && aligned(p.residual, va);
-  p.vec_store = vs ? 2 : (contiguous4 ? 1 : 0);
+  p.vec_store = vs ? 2 : 1;
   return HIDET_OK;
 }
 

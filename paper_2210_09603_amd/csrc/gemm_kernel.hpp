@@ -75,9 +75,15 @@ inline FastDiv make_fastdiv(long long d) {
   return f;
 }
 
+// Geometry of the implicit-GEMM convolution.  The GEMM column index enumerates output positions row by
+// row with every output row padded to OWP = roundup(OW, 8) columns: n = (image * OH + oh) * OWP + ow.  A
+// 16-byte chunk of the img2col matrix (8 consecutive n at 16 bits) then never leaves its output row, so
+// for stride 1 it is 8 consecutive pixels of one input row -- one load instead of eight.  Columns with
+// ow >= OW are dummies: their products are computed and never stored.
 struct ConvGeom {
-  int IC, H, W, KH, KW, sh, sw, ph, pw, OH, OW;
-  FastDiv d_khw, d_kw, d_ohw, d_ow;  // dividers by KH*KW, KW, OH*OW, OW
+  int IC, H, W, KH, KW, sh, sw, ph, pw, OH, OW, OWP;
+  int numel_x;                         // elements of the input tensor (bounds of the whole-chunk loads)
+  FastDiv d_khw, d_kw, d_owp, d_oh;    // dividers by KH*KW, KW, OWP, OH
 };
 
 struct GemmParams {
@@ -306,21 +312,69 @@ struct Operand {
     // of a chunk are in flight together instead of waiting for one another behind branches.
     T tmp[VEC];
     if constexpr (MODE == LD_IM2COL) {
-      // stored row sr = k index (ic, kh, kw), columns sc.. = output positions p (n, oh, ow).  The part
-      // that depends on p does not change from one K tile to the next and was prepared by init().
+      // stored row sr = k index (ic, kh, kw); the chunk = VEC consecutive output positions of one output
+      // row.  What depends on the positions was prepared by init(); what depends on k is computed here.
       const int kk = k0 + sr;
       const int k = kofs + kk;
       const int ic = g.d_khw.div(k), rem = k - ic * (g.KH * g.KW);
       const int kh = g.d_kw.div(rem), kw = rem - kh * g.KW;
-      const int koff = (ic * g.H + kh) * g.W + kw;
-      const int khv = kk < K ? kh : -(1 << 20);  // beyond the K range: every row test below fails
+      const int xy = pxy[q];
+      const int ih = (int)(short)(xy & 0xffff) + kh, iwf = (xy >> 16) + kw;  // input row, input column of element 0
+      const int cnt = pcnt[q];                                               // real positions in the chunk
+      const bool row_ok = kk < K && (unsigned)ih < (unsigned)g.H;
+      const int start = pofs[q] + (ic * g.H + kh) * g.W + kw;                // element offset of (ih, iwf)
+      if (g.sw <= 2 && g.numel_x >= 2 * VEC) {  // (a tensor smaller than the window has no valid window)
+        // Strides 1 and 2: element e is input pixel (ih, iwf + e * sw), so the chunk lies in one window of
+        // VEC * sw consecutive pixels.  Pixels left of the row (padding), right of it, and positions past
+        // the end of the output row read as zero: keep e in [lo, hi).
+        const int sw = g.sw;
+        int lo = iwf < 0 ? (-iwf + sw - 1) / sw : 0;
+        int hi = iwf < g.W ? (g.W - 1 - iwf) / sw + 1 : 0;
+        hi = hi < cnt ? hi : cnt;
+        if (!row_ok) hi = 0;
+        const bool any = hi > lo;
+        const bool inside = start >= 0 && start + VEC * sw <= g.numel_x;  // the whole window lies in the tensor
+        if (any && !inside) {
+          // first or last pixels of the tensor: the window would leave the allocation
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const bool ok = e >= lo && e < hi;
+            const T v = src[ok ? start + e * sw : 0];
+            tmp[e] = ok ? v : (T)0.0f;
+          }
+          return __builtin_bit_cast(u32x4, tmp);
+        }
+        // unconditional loads from a valid address; the mask makes them exact
+        const T* win = src + ((any && inside) ? start : 0);
+        u32x4 v = reinterpret_cast<const Unaligned*>(win)->v;
+        if (sw == 2) {
+          const u32x4 w = reinterpret_cast<const Unaligned*>(win + VEC)->v;
+          if constexpr (IS_F32) {
+            v = u32x4{v[0], v[2], w[0], w[2]};
+          } else {  // even 16-bit elements of the 16 loaded
+            v = u32x4{(v[0] & 0xffffu) | (v[1] << 16), (v[2] & 0xffffu) | (v[3] << 16),
+                      (w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
+          }
+        }
+        if (!any) lo = hi = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if constexpr (IS_F32) {
+            v[i] = (i >= lo && i < hi) ? v[i] : 0u;
+          } else {
+            const unsigned int m_lo = (2 * i >= lo && 2 * i < hi) ? 0x0000ffffu : 0u;
+            const unsigned int m_hi = (2 * i + 1 >= lo && 2 * i + 1 < hi) ? 0xffff0000u : 0u;
+            v[i] &= (m_lo | m_hi);
+          }
+        }
+        return v;
+      }
+      // Other strides: element e is input pixel (ih, iwf + e * sw); one clamped load per element.
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const int xy = pxy[q * VEC + e];
-        const int ih = (int)(short)(xy & 0xffff) + khv, iw = (xy >> 16) + kw;
-        const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
-        const int idx = ok ? pofs[q * VEC + e] + koff : 0;
-        const T v = src[idx];
+        const int iw = iwf + e * g.sw;
+        const bool ok = row_ok && e < cnt && (unsigned)iw < (unsigned)g.W;
+        const T v = src[ok ? start + e * g.sw : 0];
         tmp[e] = ok ? v : (T)0.0f;
       }
     } else {
@@ -389,12 +443,13 @@ struct Operand {
   struct __attribute__((packed, aligned(sizeof(T)))) Unaligned {
     u32x4 v;
   };
-  // img2col mode only, per fetched element: offset of input pixel (n, oh*sh - ph, ow*sw - pw) of channel 0
-  // from `src` (may be negative), and that pixel's row and column packed as two signed 16-bit fields
-  // (row -32768 marks an output position outside the matrix).
-  static constexpr int NP = (MODE == LD_IM2COL) ? NL * VEC : 1;
+  // img2col mode only, per chunk: offset of the input pixel (image, oh*sh - ph, ow*sw - pw) of channel 0 that
+  // element 0 of the chunk reads at (kh, kw) = (0, 0) (may be negative), that pixel's row and column packed as
+  // two signed 16-bit fields, and how many of the chunk's positions are real (ow < OW and inside the matrix).
+  static constexpr int NP = (MODE == LD_IM2COL) ? NL : 1;
   int pofs[NP];
   int pxy[NP];
+  int pcnt[NP];
 
   __device__ __forceinline__ void init(int tid, const ConvGeom& g) {
     if constexpr (MODE == LD_IM2COL) {
@@ -402,23 +457,15 @@ struct Operand {
       for (int q = 0; q < NL; ++q) {
         const tmap::Task t = LoadMap::task(tid, q);
         const int sc = t.j * VEC;
-        const int p = r0 + sc;
-        int n = g.d_ohw.div(p);
-        const int r = p - n * (g.OH * g.OW);
-        int oh = g.d_ow.div(r), ow = r - oh * g.OW;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
-          pofs[q * VEC + e] = (n * g.IC * g.H + ih0) * g.W + iw0;
-          pxy[q * VEC + e] = (sc + e < rows_left) ? ((ih0 & 0xffff) | (iw0 << 16)) : 0x8000;
-          if (++ow == g.OW) {
-            ow = 0;
-            if (++oh == g.OH) {
-              oh = 0;
-              ++n;
-            }
-          }
-        }
+        const int p = r0 + sc;                       // GEMM column of element 0
+        const int r = g.d_owp.div(p), ow = p - r * g.OWP;  // r = image * OH + oh
+        const int img = g.d_oh.div(r), oh = r - img * g.OH;
+        const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
+        pofs[q] = (img * g.IC * g.H + ih0) * g.W + iw0;
+        pxy[q] = (ih0 & 0xffff) | (iw0 << 16);
+        int cnt = g.OW - ow;
+        cnt = cnt < rows_left - sc ? cnt : rows_left - sc;
+        pcnt[q] = cnt < 0 ? 0 : (cnt > VEC ? VEC : cnt);
       }
     }
     if constexpr (MODE == LD_ELEM) {
@@ -607,7 +654,7 @@ struct Operand {
 //     offset(m, n) = row_offset(m) + col_offset(n),
 // so a lane that keeps its columns computes the column part once and the row part once per row:
 //   plain        m * ldc                    + n
-//   NCHW (conv)  m * OH*OW                  + image * OC*OH*OW + pixel          (n = image * OH*OW + pixel)
+//   NCHW (conv)  m * OH*OW                  + image * OC*OH*OW + oh * OW + ow   (n = (image * OH + oh) * OWP + ow)
 //   head split   ((b * heads) * seq + s) * d + h * seq * d + f                  (m = b*seq + s, n = h*d + f;
 //                the reshape-matmul-transpose sub-graph of transformer models, Section 3.2)
 // DYN = false compiles the run-time choice between plain and head split out of MAP_PLAIN kernels (the
@@ -616,8 +663,9 @@ struct Operand {
 template <int MAPPER, bool DYN = true>
 __device__ __forceinline__ long long col_offset(const GemmParams& p, int n) {
   if constexpr (MAPPER == MAP_NCHW) {
-    const int img = p.g.d_ohw.div(n);
-    return (long long)img * p.out_outer + (n - img * (int)p.out_inner);
+    const int r = p.g.d_owp.div(n), ow = n - r * p.g.OWP;
+    const int img = p.g.d_oh.div(r), oh = r - img * p.g.OH;
+    return (long long)img * p.out_outer + oh * p.g.OW + ow;
   } else {
     if (DYN && p.out_map != 0) {
       const int h = p.d_hd.div(n);
@@ -639,15 +687,27 @@ __device__ __forceinline__ long long row_offset(const GemmParams& p, int m, long
   }
 }
 
+// How many of the 4 columns n .. n+3 are real outputs (the rest lie beyond N, or -- convolution -- in the
+// padding of an output row).
+template <int MAPPER>
+__device__ __forceinline__ int group_valid(const GemmParams& p, int n) {
+  int left = p.N - n;
+  if constexpr (MAPPER == MAP_NCHW) {
+    const int r = p.g.d_owp.div(n < 0 ? 0 : n), ow = n - r * p.g.OWP;
+    left = left < p.g.OW - ow ? left : p.g.OW - ow;
+  }
+  return left < 0 ? 0 : (left > 4 ? 4 : left);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fused epilogue + predicated store of 4 consecutive output columns of one row.  `ccol` is
-// col_offset(n), computed by the caller once for all its rows.
+// col_offset(n) and `nvalid` is group_valid(n), computed by the caller once for all its rows.
 // ---------------------------------------------------------------------------------------------
 template <typename TO, int MAPPER, bool DYN = true>
 __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, const TO* __restrict__ R,
                                        const TO* __restrict__ bias, const float (&col_bias)[4], int m, int n,
-                                       long long ccol, const float (&acc)[4]) {
-  if (m >= p.M || n >= p.N) return;
+                                       long long ccol, int nvalid, const float (&acc)[4]) {
+  if (m >= p.M || nvalid <= 0) return;
   const bool remap = (MAPPER == MAP_NCHW) || (DYN && p.out_map != 0);
   const long long crow = row_offset<MAPPER, DYN>(p, m, p.ldc);
   const long long rrow = remap ? crow : (long long)m * p.ldr;
@@ -659,7 +719,7 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
   float v[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) v[e] = p.alpha * acc[e];
-  const bool whole = p.vec_store && (n + 3 < p.N);
+  const bool whole = p.vec_store && nvalid == 4;
   if (p.bias_axis == 2) {
     const float b = to_f32(bias[m]);
 #pragma unroll
@@ -677,9 +737,9 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if (n + e < p.N) {
-          long long ro = roff + e;
-          if (remap) ro = rrow + col_offset<MAPPER, DYN>(p, n + e);
+        if (e < nvalid) {
+          long long ro = roff + e;  // plain and NCHW: the group is contiguous
+          if (MAPPER == MAP_PLAIN && remap) ro = rrow + col_offset<MAPPER, DYN>(p, n + e);
           v[e] += to_f32(R[ro]);
         }
       }
@@ -706,9 +766,9 @@ __device__ __forceinline__ void store4(const GemmParams& p, TO* __restrict__ C, 
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      if (n + e < p.N) {
+      if (e < nvalid) {
         long long oo = off + e;
-        if (remap) oo = crow + col_offset<MAPPER, DYN>(p, n + e);
+        if (MAPPER == MAP_PLAIN && remap) oo = crow + col_offset<MAPPER, DYN>(p, n + e);
         C[oo] = o[e];
       }
     }
@@ -818,6 +878,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords&
   unsigned char* region = smem + wave * (MI * ROW_BYTES);
   const int my_n = bc.n0 + wn0 + (lane % LANES_PER_ROW) * 4;  // the same 4 columns in every read-back step
   const long long my_ccol = col_offset<Cfg::MAPPER, DYN>(p, my_n);
+  const int my_valid = group_valid<Cfg::MAPPER>(p, my_n);
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
 #pragma unroll
@@ -838,7 +899,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const BlockCoords&
       if (SLOTS % 64 == 0 || idx < SLOTS) {
         const f32x4 v = *reinterpret_cast<const f32x4*>(region + row * ROW_BYTES + c4 * 16);
         const float vv[4] = {v[0], v[1], v[2], v[3]};
-        store4<TO, Cfg::MAPPER, DYN>(p, C, R, bias, col_bias, bc.m0 + wm0 + i * MI + row, my_n, my_ccol, vv);
+        store4<TO, Cfg::MAPPER, DYN>(p, C, R, bias, col_bias, bc.m0 + wm0 + i * MI + row, my_n, my_ccol, my_valid, vv);
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
@@ -1184,7 +1245,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p) 
   }
   TO* C = reinterpret_cast<TO*>(p.C) + (long long)batch * p.strideC;
   const TO* R = p.residual ? reinterpret_cast<const TO*>(p.residual) + (long long)batch * p.strideR : nullptr;
-  store4<TO, MAPPER>(p, C, R, bias, col_bias, m, n, col_offset<MAPPER>(p, n), acc);
+  store4<TO, MAPPER>(p, C, R, bias, col_bias, m, n, col_offset<MAPPER>(p, n), group_valid<MAPPER>(p, n), acc);
 }
 
 }  // namespace hidet

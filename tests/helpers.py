@@ -99,7 +99,7 @@ def run_conv_case(c, config=-1, k_slices=None):
     if k_slices is None:
         hb.hidet_conv2d_implicit_gemm(x, w, y, stride=stride, pad=pad, epilogue=epi, config=config)
     else:
-        ws = make_workspace(1, y.shape[1], y.shape[0] * y.shape[2] * y.shape[3], k_slices)
+        ws = make_workspace(1, y.shape[1], hb.conv_gemm_n(y.shape), k_slices)
         hb.hidet_conv2d_implicit_gemm_splitk(x, w, y, ws, k_slices=k_slices, stride=stride, pad=pad, epilogue=epi,
                                              config=config)
     torch.cuda.synchronize()

@@ -188,6 +188,26 @@ def test_case_study_strided_conv_and_larger_batches():
             assert err <= TOL["f16"]
 
 
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_conv_gather_windows(dtype):
+    """Shapes chosen for the whole-chunk gather: output rows shorter than, equal to and just above one chunk, input
+    rows narrower than a chunk, wide padding (pixels left and right of the row), strides 1, 2 and 3, several images
+    (the first and the last pixels of the tensor are where a window would leave the allocation)."""
+    cases = [  # Nb, IC, H, W, OC, KH, KW, stride, pad
+        (1, 3, 7, 7, 5, 3, 3, 1, 1), (2, 4, 9, 9, 6, 3, 3, 1, 1), (1, 2, 8, 8, 4, 1, 1, 1, 0), (3, 2, 5, 3, 4, 3, 3, 1, 1),
+        (1, 3, 12, 12, 4, 5, 5, 1, 2), (2, 3, 6, 20, 4, 3, 7, 1, 3), (1, 2, 4, 4, 3, 3, 3, 1, 2), (2, 3, 15, 15, 4, 3, 3, 2, 1),
+        (1, 4, 16, 16, 4, 1, 1, 2, 0), (1, 2, 9, 30, 3, 3, 3, 2, 0), (1, 3, 17, 17, 4, 5, 5, 3, 2), (1, 1, 2, 2, 1, 1, 1, 1, 0),
+        (1, 1, 1, 9, 2, 1, 3, 1, 1), (2, 2, 3, 17, 3, 3, 3, (1, 2), (1, 0)), (1, 2, 11, 11, 3, 3, 3, (2, 1), (0, 2)),
+    ]
+    for i, (Nb, IC, H, W, OC, KH, KW, st, pd) in enumerate(cases):
+        c = wl.conv_case(7720 + i, Nb, IC, H, W, OC, KH, KW, st, pd, dtype, residual=bool(i % 2))
+        c.update(relu=bool(i % 3))
+        err, _, ref = run_conv_case(c)
+        assert within_bound(err, ref, dtype), (i, err)
+        err, _, ref = run_conv_case(c, k_slices=2, config=sliceable_configs(dtype)[i % 3])
+        assert within_bound(err, ref, dtype), (i, err)
+
+
 # ------------------------------------------------------------------ output index map (reshape-matmul-transpose)
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_head_split_output_map(dtype):
