@@ -408,6 +408,28 @@ def test_splitk_degenerate_slice_counts_and_workspace_extent():
         hb.hidet_batched_gemm_splitk(A, B, big[:45, :51], ws[:need - 1], k_slices=4, config=cfg)
 
 
+def test_splitk_repeated_calls_are_bit_identical_on_a_grid_that_spans_every_die():
+    """4096 workgroups over all compute units, then the reduce pass: slices are added in slice order, so repeated
+    calls must agree to the bit."""
+    c = wl.gemm_case(8750, 256, 4096, 4096, "f16", bias="col")
+    A, B, bias = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16"), to_gpu(c["bias"], "f16")
+    epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True)
+    cfg = [i for i in sliceable_configs("f16") if hb.hidet_config_info(i)["block_m"] == 64
+           and hb.hidet_config_info(i)["block_n"] == 32][0]
+    ws = make_workspace(1, 256, 4096, 8)
+    first = torch.empty((256, 4096), dtype=torch.float16, device="cuda")
+    hb.hidet_batched_gemm_splitk(A, B, first, ws, k_slices=8, epilogue=epi, config=cfg)
+    torch.cuda.synchronize()
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"), bias=wl.widen(c["bias"], "f16"), relu=True)
+    assert oracle.rel_frobenius(to_f64(first), ref) <= TOL["f16"]
+    C = torch.empty_like(first)
+    for i in range(20):
+        C.fill_(float("nan"))
+        hb.hidet_batched_gemm_splitk(A, B, C, ws, k_slices=8, epilogue=epi, config=cfg)
+        torch.cuda.synchronize()
+        assert torch.equal(C, first), i
+
+
 def test_splitk_batched_with_shared_operand_and_residual():
     g = wl.rng(8800)
     A = wl.normal(g, (5, 33, 640), "f16")
