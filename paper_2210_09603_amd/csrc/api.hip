@@ -278,25 +278,22 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
   return registry().fn[config][pr.dtype][kPartialVariants + variant];
 }
 
-// Untuned choice: the largest tile that still gives every compute unit a workgroup, else the tile
-// with the most workgroups.  With slices > 1 only tiles that have a K-parallel form take part.
+// Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the tile
+// with the most workgroups.  Between tiles of one size the ring schedule and the 16x16 matrix-core shape are
+// preferred (they measure faster wherever both apply).  With slices > 1 only tiles that have a K-parallel
+// form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
-  int best = -1;
-  long long best_area = -1;
-  int most = -1;
+  auto rank = [](const ConfigRow& r) { return (long long)r.bm * r.bn * 4 + (r.sched == 1 ? 2 : 0) + (r.mfma == 16 ? 1 : 0); };
+  int best = -1, most = -1;
   long long most_blocks = -1;
   for (int c = 0; c < kNumConfigs; ++c) {
     if (!find_launcher(pr, c)) continue;
     if (slices > 1 && !find_partial_launcher(pr, c)) continue;
     const ConfigRow& r = kConfigs[c];
     const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch * (slices > 1 ? slices : 1);
-    const long long area = (long long)r.bm * r.bn;
-    if (blocks >= 256 && area > best_area) {
-      best_area = area;
-      best = c;
-    }
-    if (blocks > most_blocks || (blocks == most_blocks && most >= 0 && area > (long long)kConfigs[most].bm * kConfigs[most].bn)) {
+    if (blocks >= 192 && (best < 0 || rank(r) > rank(kConfigs[best]))) best = c;
+    if (blocks > most_blocks || (blocks == most_blocks && rank(r) > rank(kConfigs[most]))) {
       most_blocks = blocks;
       most = c;
     }
