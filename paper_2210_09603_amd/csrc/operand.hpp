@@ -1,0 +1,381 @@
+// One operand tile on its way global memory -> registers -> LDS -> matrix-core fragment, with the fused
+// prologues (plain, transposed, element-aligned, img2col gather).
+#pragma once
+
+#include "config.hpp"
+
+namespace hidet {
+
+// ---------------------------------------------------------------------------------------------
+// One operand (A or B) of one workgroup: global source + LDS tile.
+//   ROWS   extent of the tile along M (for A) or N (for B)
+//   LAYOUT L_KC: element (r, k) at src[r*ld + k];  L_MC: element (k, r) at src[k*ld + r]
+// LDS layout, 16-bit types: same orientation as the source, chunk-swizzled (see swz_*).
+// LDS layout, fp32: always [k][r] (each lane reads a single float per MFMA, consecutive lanes
+// read consecutive r), so a KC source is transposed on its way into LDS.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int ROWS, int BK, int LAYOUT, int MODE, int NT, int MI>
+struct Operand {
+  static constexpr bool IS_F32 = sizeof(T) == 4;
+  static constexpr int VEC = 16 / (int)sizeof(T);
+  static constexpr int CPR = (LAYOUT == L_KC) ? BK / VEC : ROWS / VEC;  // chunks per stored row
+  static constexpr int SROWS = (LAYOUT == L_KC) ? ROWS : BK;             // stored rows
+  static constexpr int NL = ROWS * BK / VEC / NT;
+  static constexpr int KGROUPS = 64 / MI;
+  using LoadMap = typename std::conditional<(IS_F32 && LAYOUT == L_KC), LoadMapColMajor<SROWS, CPR, NT>,
+                                            LoadMapRowMajor<SROWS, CPR, NT>>::type;
+  using Frag = typename FragT<T>::type;
+
+  const T* src;      // origin of this workgroup's panel: row r0 (KC) or column r0 (MC), k = 0
+  long long ld;
+  int rows_left;     // valid extent along ROWS from the panel origin (may exceed ROWS, may be <= 0)
+  int K;             // extent of this workgroup's K range
+  int kofs;          // global k index where that range starts (needed by the img2col gather)
+  int r0;            // global row/column of the panel origin (needed by the img2col gather)
+
+  // ---- global -> registers ------------------------------------------------------------------
+  __device__ __forceinline__ u32x4 gather(int q, int sr, int sc, int k0, const ConvGeom& g) const {
+    // Element by element, zero-filled: any alignment, any edge.  Every load is issued unconditionally
+    // from a clamped (always valid) address and the predicate is applied to the value, so the VEC loads
+    // of a chunk are in flight together instead of waiting for one another behind branches.
+    T tmp[VEC];
+    if constexpr (MODE == LD_IM2COL) {
+      // stored row sr = k index (ic, kh, kw); the chunk = VEC consecutive output positions of one output
+      // row.  What depends on the positions was prepared by init(); what depends on k is computed here.
+      const int kk = k0 + sr;
+      const int k = kofs + kk;
+      const int ic = g.d_khw.div(k), rem = k - ic * (g.KH * g.KW);
+      const int kh = g.d_kw.div(rem), kw = rem - kh * g.KW;
+      const int xy = pxy[q];
+      const int ih = (int)(short)(xy & 0xffff) + kh, iwf = (xy >> 16) + kw;  // input row, input column of element 0
+      const int cnt = pcnt[q];                                               // real positions in the chunk
+      const bool row_ok = kk < K && (unsigned)ih < (unsigned)g.H;
+      const int start = pofs[q] + (ic * g.H + kh) * g.W + kw;                // element offset of (ih, iwf)
+      if (g.sw <= 2 && g.numel_x >= 2 * VEC) {  // (a tensor smaller than the window has no valid window)
+        // Strides 1 and 2: element e is input pixel (ih, iwf + e * sw), so the chunk lies in one window of
+        // VEC * sw consecutive pixels.  Pixels left of the row (padding), right of it, and positions past
+        // the end of the output row read as zero: keep e in [lo, hi).
+        const int sw = g.sw;
+        int lo = iwf < 0 ? (-iwf + sw - 1) / sw : 0;
+        int hi = iwf < g.W ? (g.W - 1 - iwf) / sw + 1 : 0;
+        hi = hi < cnt ? hi : cnt;
+        if (!row_ok) hi = 0;
+        const bool any = hi > lo;
+        const bool inside = start >= 0 && start + VEC * sw <= g.numel_x;  // the whole window lies in the tensor
+        if (any && !inside) {
+          // first or last pixels of the tensor: the window would leave the allocation
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const bool ok = e >= lo && e < hi;
+            const T v = src[ok ? start + e * sw : 0];
+            tmp[e] = ok ? v : (T)0.0f;
+          }
+          return __builtin_bit_cast(u32x4, tmp);
+        }
+        // unconditional loads from a valid address; the mask makes them exact
+        const T* win = src + ((any && inside) ? start : 0);
+        u32x4 v = reinterpret_cast<const Unaligned*>(win)->v;
+        if (sw == 2) {
+          const u32x4 w = reinterpret_cast<const Unaligned*>(win + VEC)->v;
+          if constexpr (IS_F32) {
+            v = u32x4{v[0], v[2], w[0], w[2]};
+          } else {  // even 16-bit elements of the 16 loaded
+            v = u32x4{(v[0] & 0xffffu) | (v[1] << 16), (v[2] & 0xffffu) | (v[3] << 16),
+                      (w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
+          }
+        }
+        if (!any) lo = hi = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if constexpr (IS_F32) {
+            v[i] = (i >= lo && i < hi) ? v[i] : 0u;
+          } else {
+            const unsigned int m_lo = (2 * i >= lo && 2 * i < hi) ? 0x0000ffffu : 0u;
+            const unsigned int m_hi = (2 * i + 1 >= lo && 2 * i + 1 < hi) ? 0xffff0000u : 0u;
+            v[i] &= (m_lo | m_hi);
+          }
+        }
+        return v;
+      }
+      // Other strides: element e is input pixel (ih, iwf + e * sw); one clamped load per element.
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const int iw = iwf + e * g.sw;
+        const bool ok = row_ok && e < cnt && (unsigned)iw < (unsigned)g.W;
+        const T v = src[ok ? start + e * g.sw : 0];
+        tmp[e] = ok ? v : (T)0.0f;
+      }
+    } else {
+      // Element mode: rows are not 16-byte aligned (odd leading dimension, offset pointer).  A chunk that lies
+      // entirely inside the matrix is still fetched with one 16-byte load -- the address is only element
+      // aligned, which global loads accept on this target -- and only chunks that straddle an edge fall back
+      // to one predicated load per element.
+      long long base;
+      int valid;  // elements of the chunk inside the matrix
+      bool whole;  // the 16 bytes of the chunk may be read at once
+      if constexpr (LAYOUT == L_KC) {
+        base = (long long)sr * ld + (k0 + sc);
+        valid = sr < rows_left ? K - (k0 + sc) : 0;
+        // a chunk that sticks out along K is read whole and masked below, unless it ends the last row
+        whole = valid >= VEC || (valid > 0 && (kofs + k0 + sc + VEC <= ld || sr < rows_left - 1));
+      } else {
+        base = (long long)(k0 + sr) * ld + sc;
+        valid = k0 + sr < K ? rows_left - sc : 0;
+        // a chunk that sticks out along M/N may be read whole (see init) unless it ends the last row
+        whole = valid >= VEC || (valid > 0 && (r0 + sc + VEC <= ld || k0 + sr < K - 1));
+      }
+      if (valid <= 0) return u32x4{0u, 0u, 0u, 0u};
+      if (whole) {
+        u32x4 v = reinterpret_cast<const Unaligned*>(src + base)->v;
+        if constexpr (LAYOUT == L_KC) {
+          // along K what lies beyond the matrix must contribute exact zeros
+          if (valid < VEC) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if constexpr (IS_F32)
+                v[i] = valid > i ? v[i] : 0u;
+              else
+                v[i] &= valid >= 2 * i + 2 ? 0xffffffffu : (valid == 2 * i + 1 ? 0x0000ffffu : 0u);
+            }
+          }
+        }
+        return v;
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const bool ok = e < valid;
+        const T v = src[ok ? base + e : 0];
+        tmp[e] = ok ? v : (T)0.0f;
+      }
+    }
+    return __builtin_bit_cast(u32x4, tmp);
+  }
+
+  // Vector mode (LD_VEC): the host guarantees 16-byte aligned rows and that no chunk straddles the
+  // edge of the matrix (K, resp. the M/N extent, is a multiple of the chunk length).  Chunks that lie
+  // outside the matrix along M/N are redirected to the last valid row / chunk: they only feed output
+  // rows or columns that are never stored, so any finite or non-finite value is harmless there.
+  // Along K a chunk outside the matrix must read as zero; that can only happen in the last K tile.
+  int off[NL];  // element offset of each chunk from `src` at k = 0 (vector mode only)
+  // Element mode: the same idea at element alignment.  eoff = offset of the chunk at k = 0, nv = how many
+  // of its VEC elements lie inside the matrix along M/N (a property of the chunk, not of the K tile).
+  // Chunks entirely outside are redirected to a chunk inside (nv = VEC; they feed outputs that are never
+  // stored).  A chunk that straddles the M/N edge is still read whole: the bytes past the edge are the
+  // padding of the row or the beginning of the next row -- valid memory, and values that only reach
+  // outputs that are never stored.  The exception is the last row of the operand, where "past the edge"
+  // may be past the allocation: nv = -(valid elements) marks such chunks, and the one row concerned is
+  // fetched element by element (so is everything in a matrix narrower than one chunk, 0 <= nv < VEC).
+  static constexpr int NE = (MODE == LD_ELEM) ? NL : 1;
+  long long eoff[NE];
+  int nv[NE];
+  struct __attribute__((packed, aligned(sizeof(T)))) Unaligned {
+    u32x4 v;
+  };
+  // img2col mode only, per chunk: offset of the input pixel (image, oh*sh - ph, ow*sw - pw) of channel 0 that
+  // element 0 of the chunk reads at (kh, kw) = (0, 0) (may be negative), that pixel's row and column packed as
+  // two signed 16-bit fields, and how many of the chunk's positions are real (ow < OW and inside the matrix).
+  static constexpr int NP = (MODE == LD_IM2COL) ? NL : 1;
+  int pofs[NP];
+  int pxy[NP];
+  int pcnt[NP];
+
+  __device__ __forceinline__ void init(int tid, const ConvGeom& g) {
+    if constexpr (MODE == LD_IM2COL) {
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        const int sc = t.j * VEC;
+        const int p = r0 + sc;                       // GEMM column of element 0
+        const int r = g.d_owp.div(p), ow = p - r * g.OWP;  // r = image * OH + oh
+        const int img = g.d_oh.div(r), oh = r - img * g.OH;
+        const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
+        pofs[q] = (img * g.IC * g.H + ih0) * g.W + iw0;
+        pxy[q] = (ih0 & 0xffff) | (iw0 << 16);
+        int cnt = g.OW - ow;
+        cnt = cnt < rows_left - sc ? cnt : rows_left - sc;
+        pcnt[q] = cnt < 0 ? 0 : (cnt > VEC ? VEC : cnt);
+      }
+    }
+    if constexpr (MODE == LD_ELEM) {
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        const int sr = t.i, sc = t.j * VEC;
+        if constexpr (LAYOUT == L_KC) {
+          const int r = sr < rows_left ? sr : rows_left - 1;
+          eoff[q] = (long long)r * ld + sc;
+          nv[q] = VEC;
+        } else {
+          const int rem = rows_left - sc;
+          int c = sc, n = rem;
+          if (rem >= VEC) {
+            n = VEC;
+          } else if (rem > 0) {
+            n = (r0 + sc + VEC <= ld) ? VEC : -rem;  // the padding of the row covers the over-read
+          } else {
+            n = rows_left >= VEC ? VEC : 0;  // a matrix narrower than one chunk has nowhere to redirect to
+            c = rows_left >= VEC ? rows_left - VEC : 0;
+          }
+          eoff[q] = (long long)sr * ld + c;
+          nv[q] = n;
+        }
+      }
+    }
+    if constexpr (MODE == LD_VEC) {
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        const int sr = t.i, sc = t.j * VEC;
+        if constexpr (LAYOUT == L_KC) {
+          const int r = sr < rows_left ? sr : rows_left - 1;
+          off[q] = r * (int)ld + sc;
+        } else {
+          const int c = sc + VEC <= rows_left ? sc : rows_left - VEC;
+          off[q] = sr * (int)ld + c;
+        }
+      }
+    }
+  }
+
+  // Direct global -> LDS loads (vector mode, 16-bit types).  Lane l of a wave writes its 16 bytes at
+  // LDS[base + 16*l], so the LDS side of the cooperative load is fixed -- thread t's q-th load fills
+  // stored position q*NT + t of the tile -- and the swizzle moves to the global side: the thread
+  // fetches the logical chunk that belongs at that position.  The instruction is issued through
+  // inline assembly and tracked by hand with s_waitcnt vmcnt(n): the schedule that uses it keeps
+  // several stages in flight and waits for the oldest only.
+  int doff[NL];
+  __device__ __forceinline__ void init_direct(int tid) {
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const int pos = q * NT + tid;
+      const int row = pos / CPR, pc = pos % CPR;
+      const int lc = pc ^ ((LAYOUT == L_KC) ? swz_kc<CPR, MI>(row) : swz_mc<CPR, MI>(row));
+      if constexpr (LAYOUT == L_KC) {
+        const int r = row < rows_left ? row : rows_left - 1;
+        doff[q] = r * (int)ld + lc * VEC;
+      } else {
+        const int c = lc * VEC + VEC <= rows_left ? lc * VEC : rows_left - VEC;
+        doff[q] = row * (int)ld + c;
+      }
+    }
+  }
+  // `tile_lds`: LDS byte address of the tile; `wave`: wave index (both wave-uniform).
+  __device__ __forceinline__ void load_direct(unsigned tile_lds, int wave, int k0) const {
+    const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const T* g = base + doff[q];
+      const unsigned dst = tile_lds + (unsigned)((q * NT + wave * 64) * 16);
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst) : "memory");
+    }
+  }
+
+  // A K tile that lies entirely inside the matrix: no predicates at all in vector mode.
+  __device__ __forceinline__ void load_full(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
+    if constexpr (MODE == LD_VEC) {
+      const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+#pragma unroll
+      for (int q = 0; q < NL; ++q) regs[q] = *reinterpret_cast<const u32x4*>(base + off[q]);
+    } else if constexpr (MODE == LD_ELEM) {
+      const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+#pragma unroll
+      for (int q = 0; q < NL; ++q) {
+        const tmap::Task t = LoadMap::task(tid, q);
+        if (nv[q] == VEC || (nv[q] < 0 && k0 + t.i < K - 1)) {
+          regs[q] = reinterpret_cast<const Unaligned*>(base + eoff[q])->v;
+        } else {
+          const int cnt = nv[q] < 0 ? -nv[q] : nv[q];
+          T tmp[VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const bool ok = e < cnt;
+            const T v = base[ok ? eoff[q] + e : eoff[q]];
+            tmp[e] = ok ? v : (T)0.0f;
+          }
+          regs[q] = __builtin_bit_cast(u32x4, tmp);
+        }
+      }
+    } else {
+      load_edge(regs, tid, k0, g);
+    }
+  }
+
+  // The last, partial K tile (and every tile of the element-wise modes).
+  __device__ __forceinline__ void load_edge(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const tmap::Task t = LoadMap::task(tid, q);
+      const int sr = t.i, sc = t.j * VEC;  // stored row, first stored column of the chunk
+      if constexpr (MODE == LD_VEC) {
+        const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
+        const bool inside = (LAYOUT == L_KC) ? (k0 + sc < K) : (k0 + sr < K);
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (inside) v = *reinterpret_cast<const u32x4*>(base + off[q]);
+        regs[q] = v;
+      } else {
+        regs[q] = gather(q, sr, sc, k0, g);
+      }
+    }
+  }
+
+  // ---- registers -> LDS ---------------------------------------------------------------------
+  __device__ __forceinline__ void store(const u32x4 (&regs)[NL], int tid, unsigned char* tile) const {
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const tmap::Task t = LoadMap::task(tid, q);
+      if constexpr (!IS_F32) {
+        const int swz = (LAYOUT == L_KC) ? swz_kc<CPR, MI>(t.i) : swz_mc<CPR, MI>(t.i);
+        *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = regs[q];
+      } else if constexpr (LAYOUT == L_MC) {
+        *reinterpret_cast<u32x4*>(tile + (t.i * CPR + t.j) * 16) = regs[q];
+      } else {
+        // fp32, KC source: row t.i, k = 4*t.j + e  ->  LDS [k][row]
+        unsigned int* w = reinterpret_cast<unsigned int*>(tile);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[(t.j * 4 + e) * ROWS + t.i] = regs[q][e];
+      }
+    }
+  }
+
+  // ---- LDS -> MFMA fragment -----------------------------------------------------------------
+  // Fragment `f` (rows f*MI .. f*MI+MI-1 of the wave's sub-tile starting at row `w0`), k step `ks`.
+  __device__ __forceinline__ Frag fragment(const unsigned char* tile, int lane, int w0, int f, int ks) const {
+    if constexpr (IS_F32) {
+      const int k = ks * KGROUPS + lane / MI;
+      const int r = w0 + f * MI + lane % MI;
+      return reinterpret_cast<const float*>(tile)[k * ROWS + r];
+    } else if constexpr (LAYOUT == L_KC) {
+      const int r = w0 + f * MI + lane % MI;
+      const int c = ks * KGROUPS + lane / MI;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(tile + (r * CPR + (c ^ swz_kc<CPR, MI>(r))) * 16);
+      return __builtin_bit_cast(Frag, v);
+    } else {
+      // transposing read: within each group of 16 lanes, lane s supplies the address of 4
+      // elements (k = kb + s/4, columns cb + 4*(s%4) ..+3) and receives column cb + s, k = kb..kb+3
+      const int b = lane / 16, s = lane % 16;
+      int kb, cb;
+      if constexpr (MI == 32) {
+        kb = ks * 16 + 8 * (b / 2);
+        cb = w0 + f * 32 + 16 * (b % 2);
+      } else {
+        kb = ks * 32 + 8 * b;
+        cb = w0 + f * 16;
+      }
+      const int k = kb + s / 4;
+      const int col = cb + 4 * (s % 4);
+      u32x2 h[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int kk = k + 4 * i;
+        const unsigned char* addr = tile + (kk * CPR + ((col / 8) ^ swz_mc<CPR, MI>(kk))) * 16 + (col % 8) * 2;
+        const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) i16x4*)(const_cast<unsigned char*>(addr)));
+        h[i] = __builtin_bit_cast(u32x2, v);
+      }
+      const u32x4 v = {h[0][0], h[0][1], h[1][0], h[1][1]};
+      return __builtin_bit_cast(Frag, v);
+    }
+  }
+};
+
+}  // namespace hidet
