@@ -265,14 +265,15 @@ hidet_status_t hidet_taskmap_info(int32_t index, char* expr, int32_t expr_capaci
                                   int32_t* shape1, int32_t* tasks_per_worker);
 hidet_status_t hidet_taskmap_tasks(int32_t index, int32_t worker, int32_t* tasks_ij, int32_t capacity_pairs);
 /* Block-level mapping used at launch: tile (i, j) of workgroup `w` for a tiles_m x tiles_n grid with grouping `group`. */
-/*
- * Test aid for the index arithmetic of the img2col gather and of the output index maps: the kernels divide
- * by quantities fixed at launch (KH*KW, KW, OH*OW, OW, sequence length, head dimension) with one multiply
- * and one shift; this evaluates the very same routine on the host.  0 < divisor < 2^31, 0 <= n < 2^31.
- */
-hidet_status_t hidet_host_div(int64_t divisor, int32_t n, int32_t* quotient);
 hidet_status_t hidet_block_task(int32_t tiles_m, int32_t tiles_n, int32_t group, int32_t w, int32_t* tile_i,
                                 int32_t* tile_j);
+/*
+ * Test aid for the index arithmetic of the img2col gather and of the output index maps: the kernels divide
+ * by quantities fixed at launch (KH*KW, KW, the padded output-row length, OH, sequence length, head
+ * dimension) with one multiply and one shift; this evaluates the very same routine on the host.
+ * 0 < divisor < 2^31, 0 <= n < 2^31, else HIDET_ERR_INVALID_ARG.
+ */
+hidet_status_t hidet_host_div(int64_t divisor, int32_t n, int32_t* quotient);
 
 /*
  * Matrix-core ceiling probe (measurement aid, Section 6 style reporting): every wavefront of the GPU
