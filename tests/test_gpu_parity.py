@@ -298,6 +298,27 @@ def test_batched_with_shared_operand_and_residual():
     assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
 
 
+def test_calls_run_on_the_stream_they_are_given():
+    """Work queued on a side stream must be ordered with the library's kernels on that stream, not on the default one:
+    the operands are produced on the side stream right before the call and consumed right after it."""
+    c = wl.gemm_case(8050, 300, 200, 520, "f16")
+    hostA, hostB = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16")
+    ref = oracle.gemm(wl.widen(c["A"], "f16"), wl.widen(c["B"], "f16"))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for _ in range(5):
+            A = torch.zeros_like(hostA)
+            B = torch.zeros_like(hostB)
+            C = torch.full((300, 200), float("nan"), dtype=torch.float16, device="cuda")
+            A.copy_(hostA, non_blocking=True)
+            B.copy_(hostB, non_blocking=True)
+            hb.hidet_gemm(A, B, C, stream=side)
+            out = C.double()  # consumer on the same stream
+        side.synchronize()
+    assert oracle.rel_frobenius(out.cpu().numpy(), ref) <= TOL["f16"]
+
+
 # ------------------------------------------------------------------ tuning
 def test_tuner_enumerates_the_space_and_caches(tmp_path):
     c = wl.gemm_case(8100, 128, 768, 256, "f16", bias="col")
