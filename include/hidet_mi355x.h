@@ -192,8 +192,9 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
  *                    K tiles; with one effective slice the call runs the unsliced kernel and ignores
  *                    the workspace); 1: unsliced; <= 0: take (config, k_slices) remembered by
  *                    hidet_tune_*_splitk for this problem, else unsliced.
- *   config           as for the *_cfg entry points; only configurations whose workgroup tile is at most
- *                    128x128 have a sliced form, others return HIDET_ERR_NO_CONFIG when k_slices > 1.
+ *   config           as for the *_cfg entry points; configurations whose workgroup tile is at most 128x128
+ *                    and the ring-schedule configurations have a sliced form, others return
+ *                    HIDET_ERR_NO_CONFIG when k_slices > 1.
  *
  * Errors: HIDET_ERR_INVALID_ARG if the workspace is NULL or too small for the effective slice count,
  * HIDET_ERR_ALIGNMENT if it is misaligned, HIDET_ERR_UNSUPPORTED if batch > 65535 with slicing.

@@ -54,18 +54,19 @@ void register_config(Registry& r, int index, int type_index) {
   // convolution: weights are a row-major OC x (IC*KH*KW) matrix, B is the img2col gather, C is NCHW
   v[conv_variant(0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_NCHW>>;
   v[conv_variant(1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_NCHW>>;
-  // K-parallel partial sums (fp32 out, plain map, general schedule): built for the small and medium tiles, which are
-  // the ones a problem with few output tiles and a long K wants
-  if constexpr (BM * BN <= 128 * 128) {
+  // K-parallel partial sums (fp32 out, plain map): built for the small and medium tiles, which are the ones a
+  // problem with few output tiles and a long K wants, and for the ring-schedule tiles (medium-sized problems whose
+  // tiles do not fill the device)
+  if constexpr (BM * BN <= 128 * 128 || SCHED == SCHED_PINGPONG) {
     LaunchFn* w = v + kPartialVariants;
-    w[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+    w[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
     w[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
-    w[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+    w[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
     w[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
     if constexpr (TRANS_A != 0) {
-      w[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+      w[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
       w[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
-      w[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN>>;
+      w[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
       w[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
     }
     w[conv_variant(0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_PLAIN>>;

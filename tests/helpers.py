@@ -111,9 +111,10 @@ def run_conv_case(c, config=-1, k_slices=None):
 
 
 def sliceable_configs(dtype):
-    """Configurations that have a K-parallel form (workgroup tile at most 128x128)."""
+    """Configurations that have a K-parallel form (workgroup tile at most 128x128, or the ring schedule)."""
     return [i for i in applicable_configs(dtype)
-            if hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128]
+            if hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128
+            or hb.hidet_config_info(i)["schedule"] == 1]
 
 
 def applicable_configs(dtype):

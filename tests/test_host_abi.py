@@ -154,7 +154,8 @@ def test_splitk_argument_validation():
     assert L.hidet_splitk_workspace_bytes(-1, 64, 64, 2) == -1
     sliceable = [i for i in range(hb.hidet_config_count())
                  if not hb.hidet_config_info(i)["is_f32"]
-                 and hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128][0]
+                 and hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128
+                 and hb.hidet_config_info(i)["block_k"] <= 256][0]
     need = 4 * 4 * 64 * 64
 
     def g(config=sliceable, slices=4, ws=0x10000, ws_bytes=need, K=1024, A=0x1000):
@@ -168,8 +169,8 @@ def test_splitk_argument_validation():
     assert g(A=None) == 1  # the ordinary validation still comes first
     assert g(config=10 ** 6) == 4
     big = [i for i in range(hb.hidet_config_count()) if hb.hidet_config_info(i)["block_m"] == 256
-           and not hb.hidet_config_info(i)["is_f32"]][0]
-    assert g(config=big) == 4  # large tiles have no K-parallel form
+           and hb.hidet_config_info(i)["schedule"] == 0 and not hb.hidet_config_info(i)["is_f32"]][0]
+    assert g(config=big) == 4  # large general-schedule tiles have no K-parallel form
 
     def c(slices=4, ws=0x10000, ws_bytes=4 * 4 * 8 * 64, x=0x1000):
         return L.hidet_conv2d_implicit_gemm_splitk(sliceable, slices, f16, f16, 1, 64, 8, 8, 8, 3, 3, 1, 1, 1, 1, x,
