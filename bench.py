@@ -25,6 +25,29 @@ PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}  # 256 CUs x 4 SIMDs
 MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235985819}
 
 
+def graph_time(torch, fn, reps=20, replays=10):
+    """Microseconds per call of fn, replayed from a HIP graph (reps calls per graph, `replays` replays)."""
+    fn()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        fn()
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(reps):
+                fn()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1000.0 / (reps * replays)
+
+
 def side_report(torch, hb, wl, steps=200):
     """Time the other workloads with the tuner (every configuration of the space, `steps` launches each, winner reported):
     list of dicts with us, TFLOP/s, % of peak MFMA and algorithmic GB/s."""
@@ -117,27 +140,6 @@ def side_report(torch, hb, wl, steps=200):
     # reduction template: row softmax over the attention scores (memory bound: one read, one write), then the
     # whole attention chain (scaled Q.K^T, softmax in place, S.V).  Launches are replayed from a HIP graph so that
     # the Python call overhead stays out of the timing.
-    def graph_time(fn, reps=20, replays=10):
-        fn()
-        torch.cuda.synchronize()
-        side = torch.cuda.Stream()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            fn()
-            side.synchronize()
-            with torch.cuda.graph(g, stream=side):
-                for _ in range(reps):
-                    fn()
-        g.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(replays):
-            g.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1000.0 / (reps * replays)
-
     for c in wl.config4("f16"):
         Q, Kt, V = (dev(c[k], "f16") for k in ("Q", "K", "V"))
         b, s, d = c["batch"], c["seq"], c["d"]
@@ -145,7 +147,7 @@ def side_report(torch, hb, wl, steps=200):
         ctx = torch.empty((b, s, d), dtype=torch.float16, device="cuda")
         epi = hb.make_epilogue(alpha=c["alpha"])
         hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi)
-        us = graph_time(lambda: hb.hidet_softmax_rows(scores, scores))
+        us = graph_time(torch, lambda: hb.hidet_softmax_rows(scores, scores))
         nbytes = 2 * scores.numel() * 2
         rows.append({"workload": c["name"] + "_softmax", "dtype": "f16", "us": round(us, 2), "bound": "hbm",
                      "algorithmic_GBps": round(nbytes / us * 1e-3, 1), "pct_of_8TBps": round(100 * nbytes / us * 1e-3 / 8000, 2)})
@@ -154,7 +156,7 @@ def side_report(torch, hb, wl, steps=200):
             hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi)
             hb.hidet_softmax_rows(scores, scores)
             hb.hidet_batched_gemm(scores, V, ctx)
-        us = graph_time(chain)
+        us = graph_time(torch, chain)
         flops = 4.0 * b * s * s * d
         rows.append({"workload": c["name"] + "_attention_3_kernels", "dtype": "f16", "us": round(us, 2),
                      "TFLOPs": round(flops / us * 1e-6, 2), "pct_peak_mfma": round(100 * flops / us * 1e-6 / PEAK_TFLOPS["f16"], 2)})
@@ -219,7 +221,7 @@ def studies(torch, hb, wl, steps=100):
     import numpy as np
 
     def dev(stored):
-        return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+        return None if stored is None else torch.from_numpy(np.ascontiguousarray(stored)).cuda()
 
     def tile(cfg):
         i = hb.hidet_config_info(cfg)
@@ -284,6 +286,42 @@ def studies(torch, hb, wl, steps=100):
             batches.append({"layer": "%dx%d %d->%d k%d" % (H, W, IC, OC, KH), "batch": nb, "config": best, "tile": tile(best),
                             "k_slices": slices, "us": round(us, 2), "TFLOPs": round(flops / us * 1e-6, 2)})
     out["conv_batch_1_4_8_f16"] = batches
+
+    # post-scheduling fusion (after Section 6.3.4): the fused call against the same anchor kernel with an identity
+    # epilogue followed by separate elementwise kernels (PyTorch's add and relu) for the bias and the activation
+    fusion = []
+    for c in wl.config3("f16"):
+        x, w, b = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+        y = torch.empty((c["Nb"], c["OC"], c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+        sp = dict(stride=(c["stride"], c["stride"]), pad=(c["pad"], c["pad"]))
+        epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+        cfg, _ = hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp)
+        bias4 = b.view(1, -1, 1, 1)
+
+        def unfused():
+            hb.hidet_conv2d_implicit_gemm(x, w, y, config=cfg, **sp)
+            y.add_(bias4)
+            y.relu_()
+        fused_us = graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, config=cfg, **sp))
+        fusion.append({"workload": c["name"], "fused_us": round(fused_us, 2), "unfused_3_kernels_us": round(graph_time(torch, unfused), 2)})
+    for c in wl.config2("f16"):
+        A, B, bias = dev(c["A"]), dev(c["B"]), dev(c["bias"])
+        res = dev(c["residual"]) if c["residual"] is not None else None
+        C = torch.empty((c["M"], c["N"]), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, residual=res, relu=c.get("relu", False))
+        cfg, _ = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=steps)
+
+        def unfused():
+            hb.hidet_gemm(A, B, C, config=cfg)
+            if bias is not None:
+                C.add_(bias)
+            if res is not None:
+                C.add_(res)
+            if c.get("relu", False):
+                C.relu_()
+        fused_us = graph_time(torch, lambda: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg))
+        fusion.append({"workload": c["name"], "fused_us": round(fused_us, 2), "unfused_us": round(graph_time(torch, unfused), 2)})
+    out["fused_vs_separate_elementwise_kernels_f16"] = fusion
     return out
 
 
