@@ -86,7 +86,10 @@ typedef struct {
  * transA == 0: A is stored M x K (lda >= K); transA != 0: A is stored K x M (lda >= M).
  * transB == 0: B is stored K x N (ldb >= N); transB != 0: B is stored N x K (ldb >= K).
  * `in` is the dtype of A and B, `out` the dtype of C, bias and residual.  Supported pairs:
- * (F32,F32), (F16,F16), (BF16,BF16); any other pair returns HIDET_ERR_UNSUPPORTED.
+ * (F32,F32), (F16,F16), (BF16,BF16), and (F16,F32), (BF16,F32) -- the fp32 accumulators stored without
+ * the final rounding, on the configurations that have a K-parallel form (others return
+ * HIDET_ERR_NO_CONFIG); any other pair returns HIDET_ERR_UNSUPPORTED.  The convolution takes same-type
+ * pairs only.
  * The tile configuration is the cached tuning winner for this problem if hidet_tune_gemm has
  * seen it, otherwise a size-based default.
  */

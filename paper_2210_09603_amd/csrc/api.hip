@@ -64,7 +64,8 @@ namespace {
 
 struct Problem {
   int op = 0;  // 0 gemm (batched), 1 conv
-  int dtype = 0;
+  int dtype = 0;      // input type
+  int wide_out = 0;   // 1: 16-bit inputs, fp32 output (and fp32 bias / residual)
   int transA = 0, transB = 0;
   long long batch = 1;
   int elem_mode = 0;  // 1: some operand is not 16-byte aligned -> element loads
@@ -78,9 +79,10 @@ bool aligned(const void* ptr, size_t a) { return (reinterpret_cast<uintptr_t>(pt
 constexpr long long kIntMax = 2147483647LL;
 constexpr long long kMaxVecLd = 4LL << 20;  // in-tile element offsets (row * ld + col, row < 256) stay below 2^31
 
-hidet_status_t check_dtypes(int in, int out) {
+// GEMM: the output has the input type, or is fp32 for 16-bit inputs.  Convolution: same type only.
+hidet_status_t check_dtypes(int in, int out, bool conv) {
   if (in < 0 || in > 2 || out < 0 || out > 2) return HIDET_ERR_INVALID_ARG;
-  if (in != out) return HIDET_ERR_UNSUPPORTED;
+  if (in != out && (conv || out != HIDET_F32)) return HIDET_ERR_UNSUPPORTED;
   return HIDET_OK;
 }
 
@@ -125,7 +127,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
                                  long long N, long long K, const void* A, long long lda, long long strideA,
                                  const void* B, long long ldb, long long strideB, void* C, long long ldc,
                                  long long strideC, const hidet_epilogue_t* epi) {
-  hidet_status_t st = check_dtypes(in, out);
+  hidet_status_t st = check_dtypes(in, out, false);
   if (st != HIDET_OK) return st;
   if (batch < 0 || M < 0 || N < 0 || K < 0) return HIDET_ERR_INVALID_ARG;
   if (M > kIntMax || N > kIntMax || K > kIntMax || batch > kIntMax) return HIDET_ERR_UNSUPPORTED;
@@ -149,10 +151,11 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
       if (epi->batch_stride_residual < 0) return HIDET_ERR_INVALID_ARG;
     }
     const size_t es = (size_t)elem_size(in);
-    if (!aligned(A, es) || !aligned(B, es) || !aligned(C, es)) return HIDET_ERR_ALIGNMENT;
+    if (!aligned(A, es) || !aligned(B, es) || !aligned(C, (size_t)elem_size(out))) return HIDET_ERR_ALIGNMENT;
   }
   pr.op = 0;
   pr.dtype = in;
+  pr.wide_out = (in != out) ? 1 : 0;
   pr.transA = transA ? 1 : 0;
   pr.transB = transB ? 1 : 0;
   pr.batch = batch;
@@ -201,7 +204,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
 hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, long long IC, long long H, long long W,
                                  long long OC, long long KH, long long KW, long long sh, long long sw, long long ph,
                                  long long pw, const void* x, const void* w, void* y, const hidet_epilogue_t* epi) {
-  hidet_status_t st = check_dtypes(in, out);
+  hidet_status_t st = check_dtypes(in, out, true);
   if (st != HIDET_OK) return st;
   if (Nb < 0 || IC < 0 || H < 0 || W < 0 || OC < 0 || KH <= 0 || KW <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
     return HIDET_ERR_INVALID_ARG;
@@ -226,6 +229,7 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   }
   pr.op = 1;
   pr.dtype = in;
+  pr.wide_out = 0;
   pr.transA = 0;
   pr.transB = 0;
   pr.batch = 1;
@@ -267,7 +271,9 @@ LaunchFn find_launcher(const Problem& pr, int config) {
   // general-schedule kernel (the element-mode variant, which is as fast as vector mode on aligned operands).
   const int elem = (pr.p.out_map != 0 && kConfigs[config].sched == 1) ? 1 : pr.elem_mode;
   const int variant = pr.op == 1 ? conv_variant(elem) : gemm_variant(pr.transA, pr.transB, elem);
-  return registry().fn[config][pr.dtype][variant];
+  // fp32 output from 16-bit inputs: the kernels that the K-parallel form uses for its partial sums are ordinary
+  // kernels with an fp32 output type
+  return registry().fn[config][pr.dtype][(pr.wide_out ? kPartialVariants : 0) + variant];
 }
 
 // Size-based default when the problem has not been tuned: the largest tile that still yields at
@@ -313,7 +319,8 @@ std::vector<float> g_last_times;
 std::string problem_key(const Problem& pr, bool with_workspace = false) {
   char buf[256];
   const GemmParams& p = pr.p;
-  const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0) | (p.out_map ? 32 : 0);
+  const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0) |
+                       (p.out_map ? 32 : 0) | (pr.wide_out ? 64 : 0);
   if (pr.op == 0)
     std::snprintf(buf, sizeof(buf), "gemm:t%d:%d%d:b%lld:%dx%dx%d:e%d:m%d", pr.dtype, pr.transA, pr.transB, pr.batch, p.M,
                   p.N, p.K, epi_kind, pr.elem_mode);
@@ -408,8 +415,9 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
   GemmParams rp = p;
   rp.A = sk.workspace;
   rp.k_slices = (int)actual;
-  const hipError_t e = pr.op == 1 ? reduce_dispatch<MAP_NCHW>(pr.dtype, rp, (int)pr.batch, stream)
-                                  : reduce_dispatch<MAP_PLAIN>(pr.dtype, rp, (int)pr.batch, stream);
+  const int out_type = pr.wide_out ? (int)HIDET_F32 : pr.dtype;
+  const hipError_t e = pr.op == 1 ? reduce_dispatch<MAP_NCHW>(out_type, rp, (int)pr.batch, stream)
+                                  : reduce_dispatch<MAP_PLAIN>(out_type, rp, (int)pr.batch, stream);
   return e == hipSuccess ? HIDET_OK : HIDET_ERR_LAUNCH;
 }
 

@@ -298,6 +298,37 @@ def test_batched_with_shared_operand_and_residual():
     assert oracle.rel_frobenius(to_f64(C), ref) <= TOL["f16"]
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_fp32_output_from_16_bit_inputs(dtype):
+    """The accumulators stored without the final rounding: bias and residual are fp32 too, and the error against the
+    oracle is that of the fp32 accumulation alone."""
+    g = wl.rng(8060)
+    for (M, N, K, tB) in ((150, 203, 333, False), (64, 136, 1024, True)):
+        c = wl.gemm_case(8061 + M, M, N, K, dtype, transB=tB)
+        A, B = to_gpu(c["A"], dtype), to_gpu(c["B"], dtype)
+        Av, Bv = A[:, :K], (B[:, :K] if tB else B[:, :N])
+        bias = torch.from_numpy(g.standard_normal(N).astype(np.float32)).cuda()
+        res = torch.from_numpy(g.standard_normal((M, N)).astype(np.float32)).cuda()
+        A64, B64 = wl.widen(c["A"], dtype)[:, :K], (wl.widen(c["B"], dtype)[:, :K] if tB else wl.widen(c["B"], dtype)[:, :N])
+        ref = oracle.gemm(A64, B64, transB=tB, alpha=0.5, bias=bias.cpu().double().numpy(),
+                          residual=res.cpu().double().numpy(), relu=True)
+        epi = hb.make_epilogue(alpha=0.5, bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, residual=res, relu=True)
+        for cfg in [-1] + sliceable_configs(dtype):
+            C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            hb.hidet_gemm(Av, Bv, C, transB=tB, epilogue=epi, config=cfg)
+            torch.cuda.synchronize()
+            err = oracle.rel_frobenius(to_f64(C), ref)
+            assert err <= 1e-5, (cfg, err)
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        hb.hidet_batched_gemm_splitk(Av, Bv, C, make_workspace(1, M, N, 3), k_slices=3, transB=tB, epilogue=epi,
+                                     config=sliceable_configs(dtype)[0])
+        torch.cuda.synchronize()
+        assert oracle.rel_frobenius(to_f64(C), ref) <= 1e-5
+        big = [i for i in applicable_configs(dtype) if i not in sliceable_configs(dtype)][0]
+        with pytest.raises(hb.HidetError):
+            hb.hidet_gemm(Av, Bv, C, transB=tB, epilogue=epi, config=big)
+
+
 def test_calls_run_on_the_stream_they_are_given():
     """Work queued on a side stream must be ordered with the library's kernels on that stream, not on the default one:
     the operands are produced on the side stream right before the call and consumed right after it."""

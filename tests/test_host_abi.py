@@ -68,7 +68,9 @@ def test_gemm_argument_validation_happens_before_any_launch():
     assert _gemm(L, ldc=7) == INVALID
     assert _gemm(L, tA=1, M=16, lda=8) == INVALID  # transposed A is K x M: lda >= M
     assert _gemm(L, i=7) == INVALID
-    assert _gemm(L, i=hb.HIDET_F16, o=hb.HIDET_F32) == UNSUPPORTED
+    assert _gemm(L, i=hb.HIDET_F32, o=hb.HIDET_F16) == UNSUPPORTED
+    assert _gemm(L, i=hb.HIDET_F16, o=hb.HIDET_BF16) == UNSUPPORTED
+    assert _gemm(L, i=hb.HIDET_F16, o=hb.HIDET_F32, C=0x3002) == ALIGN  # fp32 output: 4-byte aligned C
     assert _gemm(L, M=2 ** 31) == UNSUPPORTED
     assert _gemm(L, A=0x1001) == ALIGN
     assert _gemm(L, i=hb.HIDET_F32, o=hb.HIDET_F32, C=0x3002) == ALIGN
@@ -126,6 +128,7 @@ def test_batched_and_conv_argument_validation():
         k.get("KH", 3), k.get("KW", 3), k.get("sh", 1), k.get("sw", 1), k.get("ph", 1), k.get("pw", 1), k.get("x", 0x1000),
         k.get("w", 0x2000), k.get("y", 0x3000), k.get("epi", None), None)
     assert conv(x=None) == 1
+    assert conv(o=hb.HIDET_F32) == 2  # the convolution takes same-type pairs only
     assert conv(sh=0) == 1
     assert conv(KH=0) == 1
     assert conv(ph=-1) == 1
