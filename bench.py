@@ -22,7 +22,7 @@ PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}  # 256 CUs x 4 SIMDs
 
 # HBM bytes per launch of the dominant kernel at 4096^3, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
 # scaled by a plain copy of known size (profiles/gemm_pingpong_f16_4096.md); None for workloads not measured.
-MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235985819}
+MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235271132}
 
 
 def graph_time(torch, fn, reps=20, replays=10):
