@@ -278,3 +278,11 @@ def test_block_level_mapping_is_a_permutation_and_groups_rows():
         rows = {t[0] for t in tasks[s:s + 32]}
         cols = {t[1] for t in tasks[s:s + 32]}
         assert len(rows) == 4 and len(cols) == 8
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
