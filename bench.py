@@ -76,9 +76,20 @@ def side_report(torch, hb, wl, steps=200):
             sliced = tune_sliced()
         return us, cfg, tune_s, sliced
 
-    rows = []
+    rows = [{"workload": "empty_kernel_launch_floor", "dtype": "-", "us": round(hb.hidet_probe_launch_floor(2000), 2)}]
 
-    def add(name, dt, flops, nbytes, us, cfg, tune_s, sliced=None):
+    def cold(call, tensors, nbytes):
+        """Microseconds per call when every call finds its operands in HBM only: the call walks over enough copies of
+        its operand set to exceed the 256 MB Infinity Cache twice (unsliced kernel, tuned tile, replayed from a graph)."""
+        n = max(2, min(256, int(600e6 // max(nbytes, 1)) + 1))
+        sets = [[t.clone() for t in tensors] for _ in range(n)]
+
+        def sweep():
+            for ts in sets:
+                call(*ts)
+        return graph_time(torch, sweep, reps=1, replays=10) / n
+
+    def add(name, dt, flops, nbytes, us, cfg, tune_s, sliced=None, us_cold=None):
         unsliced_us = us
         slices = 1
         if sliced is not None and sliced[2] < us:
@@ -91,6 +102,8 @@ def side_report(torch, hb, wl, steps=200):
                      "tile_config": cfg, "tile": "%dx%dx%d/%dx%d/mfma%d" % (info["block_m"], info["block_n"], info["block_k"],
                                                                             info["waves_m"], info["waves_n"], info["mfma"]),
                      "tuning_seconds": round(tune_s, 3)})
+        if us_cold is not None:
+            rows[-1]["us_cold_unsliced"] = round(us_cold, 2)
 
     def gemm_row(c):
         dt = c["dtype"]
@@ -104,7 +117,10 @@ def side_report(torch, hb, wl, steps=200):
                                 lambda: hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=steps),
                                 lambda: hb.hidet_tune_gemm_splitk(A, B, C, ws, epilogue=epi, iters=steps), c["M"] * c["N"])
         nbytes = (c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] * (2 if res is not None else 1)) * es
-        add(c["name"], dt, 2.0 * c["M"] * c["N"] * c["K"], nbytes, us, cfg, ts, sl)
+        uc = None
+        if nbytes < (64 << 20):  # the small, bandwidth- or latency-bound workloads
+            uc = cold(lambda a, b_, c_: hb.hidet_gemm(a, b_, c_, epilogue=epi, config=cfg), [A, B, C], nbytes)
+        add(c["name"], dt, 2.0 * c["M"] * c["N"] * c["K"], nbytes, us, cfg, ts, sl, uc)
 
     for c in wl.config1():
         gemm_row(c)
@@ -120,7 +136,9 @@ def side_report(torch, hb, wl, steps=200):
                                 lambda: hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp),
                                 lambda: hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=steps, **sp), y.numel())
         flops = 2.0 * c["Nb"] * c["OC"] * c["OH"] * c["OW"] * c["IC"] * c["KH"] * c["KW"]
-        add(c["name"], "f16", flops, (x.numel() + w.numel() + y.numel()) * 2, us, cfg, ts, sl)
+        nbytes = (x.numel() + w.numel() + y.numel()) * 2
+        uc = cold(lambda x_, w_, y_: hb.hidet_conv2d_implicit_gemm(x_, w_, y_, epilogue=epi, config=cfg, **sp), [x, w, y], nbytes)
+        add(c["name"], "f16", flops, nbytes, us, cfg, ts, sl, uc)
     for c in wl.config4("f16"):
         Q, Kt, V, S = (dev(c[k], "f16") for k in ("Q", "K", "V", "S"))
         b, s, d = c["batch"], c["seq"], c["d"]
@@ -129,10 +147,14 @@ def side_report(torch, hb, wl, steps=200):
         epi = hb.make_epilogue(alpha=c["alpha"])
         us, cfg, ts, _ = timed(lambda cfg: hb.hidet_batched_gemm(Q, Kt, scores, transB=True, epilogue=epi, config=cfg),
                                lambda: hb.hidet_tune_gemm(Q, Kt, scores, transB=True, epilogue=epi, iters=steps))
-        add(c["name"] + "_QKt", "f16", 2.0 * b * s * s * d, (2 * b * s * d + b * s * s) * 2, us, cfg, ts)
+        nbytes = (2 * b * s * d + b * s * s) * 2
+        uc = cold(lambda q_, k_, o_: hb.hidet_batched_gemm(q_, k_, o_, transB=True, epilogue=epi, config=cfg),
+                  [Q, Kt, scores], nbytes)
+        add(c["name"] + "_QKt", "f16", 2.0 * b * s * s * d, nbytes, us, cfg, ts, None, uc)
         us, cfg, ts, _ = timed(lambda cfg: hb.hidet_batched_gemm(S, V, ctx, config=cfg),
                                lambda: hb.hidet_tune_gemm(S, V, ctx, iters=steps))
-        add(c["name"] + "_SV", "f16", 2.0 * b * s * s * d, (2 * b * s * d + b * s * s) * 2, us, cfg, ts)
+        uc = cold(lambda s_, v_, o_: hb.hidet_batched_gemm(s_, v_, o_, config=cfg), [S, V, ctx], nbytes)
+        add(c["name"] + "_SV", "f16", 2.0 * b * s * s * d, nbytes, us, cfg, ts, None, uc)
     for dt in ("f16", "bf16"):
         for K in (4096, 1024):
             gemm_row(wl.config5(dt, K=K))

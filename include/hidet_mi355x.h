@@ -291,6 +291,12 @@ hidet_status_t hidet_probe_mfma_peak(int32_t dtype, int32_t mfma, const void* sa
                                      void* scratch, int64_t scratch_bytes, void* stream, float* tflops,
                                      float* sclk_mhz);
 int64_t hidet_probe_scratch_bytes(void);
+/*
+ * Launch floor (measurement aid): mean microseconds per launch of `iters` back-to-back launches of an empty
+ * kernel on `stream` -- what any kernel on this machine costs before it does anything; the small workloads
+ * are reported next to it.  Synchronises `stream`.  HIDET_ERR_INVALID_ARG for iters <= 0 or a NULL result.
+ */
+hidet_status_t hidet_probe_launch_floor(void* stream, int32_t iters, float* us_per_launch);
 
 const char* hidet_status_string(int32_t status);
 /* Library version string and the GPU architecture the kernels were compiled for ("gfx950"). */

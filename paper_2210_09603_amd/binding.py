@@ -57,7 +57,7 @@ EXPORTS = (
     "hidet_conv2d_implicit_gemm_cfg", "hidet_config_count", "hidet_config_info", "hidet_tune_gemm", "hidet_tune_conv2d",
     "hidet_tune_last_times", "hidet_tune_clear", "hidet_tune_save", "hidet_tune_load", "hidet_taskmap_count",
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
-    "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
+    "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_probe_launch_floor", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
     "hidet_softmax_rows", "hidet_host_div",
 )
@@ -108,6 +108,7 @@ def lib():
         L.hidet_probe_mfma_peak.argtypes = [_i32, _i32, _vp, _i64, _vp, _i64, _vp, ctypes.POINTER(ctypes.c_float),
                                             ctypes.POINTER(ctypes.c_float)]
         L.hidet_probe_scratch_bytes.restype = _i64
+        L.hidet_probe_launch_floor.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_float)]
         L.hidet_status_string.argtypes = [_i32]
         L.hidet_status_string.restype = ctypes.c_char_p
         L.hidet_version.restype = ctypes.c_char_p
@@ -412,6 +413,13 @@ def hidet_block_task(tiles_m, tiles_n, group, w):
     i, j = _i32(), _i32()
     _check(lib().hidet_block_task(tiles_m, tiles_n, group, w, ctypes.byref(i), ctypes.byref(j)), "hidet_block_task")
     return i.value, j.value
+
+
+def hidet_probe_launch_floor(iters=1000, stream=None):
+    """Microseconds per launch of an empty kernel (back-to-back launches on one stream)."""
+    us = ctypes.c_float(0.0)
+    _check(lib().hidet_probe_launch_floor(_stream(stream), iters, ctypes.byref(us)), "hidet_probe_launch_floor")
+    return us.value
 
 
 def hidet_probe_mfma_peak(sample, mfma=16, stream=None):

@@ -47,6 +47,8 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(const T* samp
   }
 }
 
+__global__ void empty_kernel() {}
+
 template <typename T, int MI>
 hidet_status_t run_probe(const void* sample, long long sample_bytes, void* scratch, hipStream_t stream, float* tflops,
                          float* sclk_mhz) {
@@ -106,3 +108,23 @@ extern "C" hidet_status_t hidet_probe_mfma_peak(int32_t dtype, int32_t mfma, con
 }
 
 extern "C" int64_t hidet_probe_scratch_bytes(void) { return (int64_t)kProbeBlocks * kProbeThreads * 4 + 64; }
+
+// Launch floor: `iters` launches of a kernel that does nothing, back to back on `stream`, between two events.
+extern "C" hidet_status_t hidet_probe_launch_floor(void* stream, int32_t iters, float* us_per_launch) {
+  if (iters <= 0 || !us_per_launch) return HIDET_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return HIDET_ERR_LAUNCH;
+  for (int i = 0; i < 10; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, s);
+  (void)hipEventRecord(e0, s);
+  for (int i = 0; i < iters; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, s);
+  (void)hipEventRecord(e1, s);
+  float ms = 0.0f;
+  const bool ok = hipGetLastError() == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+                  hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok) return HIDET_ERR_LAUNCH;
+  *us_per_launch = ms * 1000.0f / (float)iters;
+  return HIDET_OK;
+}

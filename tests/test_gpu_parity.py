@@ -536,3 +536,6 @@ def test_mfma_ceiling_probe_reports_plausible_numbers():
         assert 200.0 < tflops < 2600.0 and 500.0 < mhz < 2600.0
     t32, _ = hb.hidet_probe_mfma_peak(torch.rand(1 << 14, device="cuda"), mfma=32)
     assert 20.0 < t32 < 160.0
+    floor = hb.hidet_probe_launch_floor(500)
+    _say("launch floor %.2f us" % floor)
+    assert 0.5 < floor < 50.0
