@@ -92,6 +92,8 @@ typedef struct {
  * pairs only.
  * The tile configuration is the cached tuning winner for this problem if hidet_tune_gemm has
  * seen it, otherwise a size-based default.
+ * Limits (HIDET_ERR_UNSUPPORTED beyond them): M, N and K are at most 2^31 - 65537 each; the number of
+ * elements of A, B and C is not limited (offsets are 64-bit).
  */
 hidet_status_t hidet_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M, int64_t N, int64_t K,
                           const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
@@ -116,8 +118,9 @@ hidet_status_t hidet_batched_gemm(int32_t in, int32_t out, int32_t transA, int32
  * fused epilogue, so no img2col matrix is ever materialised.  In the epilogue, bias (if any) must
  * be HIDET_BIAS_PER_ROW, i.e. one value per output channel, and residual (if any) is a dense
  * tensor of y's shape (ld_residual and batch_stride_residual are ignored).
- * Limits (HIDET_ERR_UNSUPPORTED beyond them): x has fewer than 2^31 elements, H + 2*pad_h, W + 2*pad_w,
- * KH and KW are at most 32767, and OC, Nb*OH*OW and IC*KH*KW are below 2^31.
+ * Limits (HIDET_ERR_UNSUPPORTED beyond them): x has at most 2^31 - 65537 elements (y may have more),
+ * H + 2*pad_h, W + 2*pad_w, KH and KW are at most 32767, and OC, Nb*OH*roundup(OW, 8) and IC*KH*KW are
+ * at most 2^31 - 65537.
  */
 hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
                                           int64_t OC, int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,

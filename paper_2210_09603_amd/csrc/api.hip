@@ -77,6 +77,9 @@ struct Problem {
 int elem_size(int dtype) { return dtype == HIDET_F32 ? 4 : 2; }
 bool aligned(const void* ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; }
 constexpr long long kIntMax = 2147483647LL;
+// Largest extent of a GEMM dimension (and of the input tensor of a convolution, in elements): the kernels keep
+// such indices in 32 bits and step past them by at most one tile (or one gather window) before comparing.
+constexpr long long kMaxDim = kIntMax - 65536;
 constexpr long long kMaxVecLd = 4LL << 20;  // in-tile element offsets (row * ld + col, row < 256) stay below 2^31
 
 // GEMM: the output has the input type, or is fp32 for 16-bit inputs.  Convolution: same type only.
@@ -130,7 +133,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
   hidet_status_t st = check_dtypes(in, out, false);
   if (st != HIDET_OK) return st;
   if (batch < 0 || M < 0 || N < 0 || K < 0) return HIDET_ERR_INVALID_ARG;
-  if (M > kIntMax || N > kIntMax || K > kIntMax || batch > kIntMax) return HIDET_ERR_UNSUPPORTED;
+  if (M > kMaxDim || N > kMaxDim || K > kMaxDim || batch > kIntMax) return HIDET_ERR_UNSUPPORTED;
   const bool empty = (batch == 0 || M == 0 || N == 0);
   st = check_epilogue(epi, out, false);
   if (st != HIDET_OK) return st;
@@ -217,7 +220,7 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   const long long M = OC, N = Nb * OH * OWP, K = IC * KH * KW;
   // the gather keeps input rows and columns (padding included) in signed 16-bit fields and element
   // offsets in 32 bits
-  if (M > kIntMax || N > kIntMax || K > kIntMax || Nb * IC * H * W > kIntMax || H + 2 * ph > 32767 ||
+  if (M > kMaxDim || N > kMaxDim || K > kMaxDim || Nb * IC * H * W > kMaxDim || H + 2 * ph > 32767 ||
       W + 2 * pw > 32767 || KH > 32767 || KW > 32767)
     return HIDET_ERR_UNSUPPORTED;
   const bool empty = (M == 0 || N == 0);

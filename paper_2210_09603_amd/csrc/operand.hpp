@@ -189,11 +189,13 @@ struct Operand {
         const int r = g.d_owp.div(p), ow = p - r * g.OWP;  // r = image * OH + oh
         const int img = g.d_oh.div(r), oh = r - img * g.OH;
         const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
-        pofs[q] = (img * g.IC * g.H + ih0) * g.W + iw0;
-        pxy[q] = (ih0 & 0xffff) | (iw0 << 16);
         int cnt = g.OW - ow;
         cnt = cnt < rows_left - sc ? cnt : rows_left - sc;
-        pcnt[q] = cnt < 0 ? 0 : (cnt > VEC ? VEC : cnt);
+        cnt = cnt < 0 ? 0 : (cnt > VEC ? VEC : cnt);
+        pcnt[q] = cnt;
+        // (a chunk with no real position may lie past the last image, where the offset would leave 32 bits)
+        pofs[q] = cnt > 0 ? (img * g.IC * g.H + ih0) * g.W + iw0 : 0;
+        pxy[q] = (ih0 & 0xffff) | (iw0 << 16);
       }
     }
     if constexpr (MODE == LD_ELEM) {

@@ -72,6 +72,10 @@ def test_gemm_argument_validation_happens_before_any_launch():
     assert _gemm(L, i=hb.HIDET_F16, o=hb.HIDET_BF16) == UNSUPPORTED
     assert _gemm(L, i=hb.HIDET_F16, o=hb.HIDET_F32, C=0x3002) == ALIGN  # fp32 output: 4-byte aligned C
     assert _gemm(L, M=2 ** 31) == UNSUPPORTED
+    # 32-bit indices step at most one tile past an extent, so the largest extent stays that far below 2^31
+    assert _gemm(L, M=2 ** 31 - 65536, lda=8) == UNSUPPORTED
+    assert _gemm(L, K=2 ** 31 - 65536, lda=2 ** 31, ldb=8) == UNSUPPORTED
+    assert _gemm(L, N=2 ** 31 - 65536, ldb=2 ** 31, ldc=2 ** 31) == UNSUPPORTED
     assert _gemm(L, A=0x1001) == ALIGN
     assert _gemm(L, i=hb.HIDET_F32, o=hb.HIDET_F32, C=0x3002) == ALIGN
     assert _gemm(L, config=10 ** 6) == NOCFG
@@ -144,6 +148,7 @@ def test_batched_and_conv_argument_validation():
     e.map_seq, e.map_head_dim = 1, 1
     assert conv(epi=ctypes.byref(e)) == 1
     assert conv(H=40000) == 2 and conv(pw=20000) == 2  # rows/columns are kept in 16-bit fields
+    assert conv(IC=331, H=14322, W=453) == 2  # x has 2^31 - 2 elements: a gather window could step past 2^31
     assert hb.lib().hidet_status_string(3) == b"misaligned pointer"
 
 
