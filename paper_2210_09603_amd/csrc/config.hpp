@@ -32,7 +32,10 @@ struct GemmConfig {
   static constexpr int STAGES = (SCHED == SCHED_PINGPONG) ? 4 : 2;
   // per-wave transposition regions of the epilogue: MI rows of the wave tile in fp32, rows padded by 16 bytes
   static constexpr int EPI_BYTES = NWAVES * MI * (WTN * 4 + 16);
-  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
+  // img2col gather: table of the 16-byte masks that keep elements [lo, hi) of a chunk, behind the stages
+  static constexpr int MASK_BYTES = (MODE_B == LD_IM2COL) ? (VEC + 1) * (VEC + 1) * 16 : 0;
+  static constexpr int MAIN_BYTES = STAGES * STAGE_BYTES + MASK_BYTES;
+  static constexpr int LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
   static constexpr int NL_A = BM * BK / VEC / NT;  // chunks per thread per tile
   static constexpr int NL_B = BN * BK / VEC / NT;
   static_assert(BM % (WAVES_M * MI) == 0 && BN % (WAVES_N * MI) == 0, "wave tiles must be whole MFMA tiles");

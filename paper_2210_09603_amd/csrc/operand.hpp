@@ -35,77 +35,11 @@ struct Operand {
 
   // ---- global -> registers ------------------------------------------------------------------
   __device__ __forceinline__ u32x4 gather(int q, int sr, int sc, int k0, const ConvGeom& g) const {
-    // Element by element, zero-filled: any alignment, any edge.  Every load is issued unconditionally
-    // from a clamped (always valid) address and the predicate is applied to the value, so the VEC loads
-    // of a chunk are in flight together instead of waiting for one another behind branches.
+    // Every load is issued unconditionally from a clamped (always valid) address and the predicate is
+    // applied to the value, so the VEC loads of a chunk are in flight together instead of waiting for one
+    // another behind branches.
     T tmp[VEC];
-    if constexpr (MODE == LD_IM2COL) {
-      // stored row sr = k index (ic, kh, kw); the chunk = VEC consecutive output positions of one output
-      // row.  What depends on the positions was prepared by init(); what depends on k is computed here.
-      const int kk = k0 + sr;
-      const int k = kofs + kk;
-      const int ic = g.d_khw.div(k), rem = k - ic * (g.KH * g.KW);
-      const int kh = g.d_kw.div(rem), kw = rem - kh * g.KW;
-      const int xy = pxy[q];
-      const int ih = (int)(short)(xy & 0xffff) + kh, iwf = (xy >> 16) + kw;  // input row, input column of element 0
-      const int cnt = pcnt[q];                                               // real positions in the chunk
-      const bool row_ok = kk < K && (unsigned)ih < (unsigned)g.H;
-      const int start = pofs[q] + (ic * g.H + kh) * g.W + kw;                // element offset of (ih, iwf)
-      if (g.sw <= 2 && g.numel_x >= 2 * VEC) {  // (a tensor smaller than the window has no valid window)
-        // Strides 1 and 2: element e is input pixel (ih, iwf + e * sw), so the chunk lies in one window of
-        // VEC * sw consecutive pixels.  Pixels left of the row (padding), right of it, and positions past
-        // the end of the output row read as zero: keep e in [lo, hi).
-        const int sw = g.sw;
-        int lo = iwf < 0 ? (-iwf + sw - 1) / sw : 0;
-        int hi = iwf < g.W ? (g.W - 1 - iwf) / sw + 1 : 0;
-        hi = hi < cnt ? hi : cnt;
-        if (!row_ok) hi = 0;
-        const bool any = hi > lo;
-        const bool inside = start >= 0 && start + VEC * sw <= g.numel_x;  // the whole window lies in the tensor
-        if (any && !inside) {
-          // first or last pixels of the tensor: the window would leave the allocation
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) {
-            const bool ok = e >= lo && e < hi;
-            const T v = src[ok ? start + e * sw : 0];
-            tmp[e] = ok ? v : (T)0.0f;
-          }
-          return __builtin_bit_cast(u32x4, tmp);
-        }
-        // unconditional loads from a valid address; the mask makes them exact
-        const T* win = src + ((any && inside) ? start : 0);
-        u32x4 v = reinterpret_cast<const Unaligned*>(win)->v;
-        if (sw == 2) {
-          const u32x4 w = reinterpret_cast<const Unaligned*>(win + VEC)->v;
-          if constexpr (IS_F32) {
-            v = u32x4{v[0], v[2], w[0], w[2]};
-          } else {  // even 16-bit elements of the 16 loaded
-            v = u32x4{(v[0] & 0xffffu) | (v[1] << 16), (v[2] & 0xffffu) | (v[3] << 16),
-                      (w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
-          }
-        }
-        if (!any) lo = hi = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if constexpr (IS_F32) {
-            v[i] = (i >= lo && i < hi) ? v[i] : 0u;
-          } else {
-            const unsigned int m_lo = (2 * i >= lo && 2 * i < hi) ? 0x0000ffffu : 0u;
-            const unsigned int m_hi = (2 * i + 1 >= lo && 2 * i + 1 < hi) ? 0xffff0000u : 0u;
-            v[i] &= (m_lo | m_hi);
-          }
-        }
-        return v;
-      }
-      // Other strides: element e is input pixel (ih, iwf + e * sw); one clamped load per element.
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        const int iw = iwf + e * g.sw;
-        const bool ok = row_ok && e < cnt && (unsigned)iw < (unsigned)g.W;
-        const T v = src[ok ? start + e * g.sw : 0];
-        tmp[e] = ok ? v : (T)0.0f;
-      }
-    } else {
+    {
       // Element mode: rows are not 16-byte aligned (odd leading dimension, offset pointer).  A chunk that lies
       // entirely inside the matrix is still fetched with one 16-byte load -- the address is only element
       // aligned, which global loads accept on this target -- and only chunks that straddle an edge fall back
@@ -171,32 +105,142 @@ struct Operand {
   struct __attribute__((packed, aligned(sizeof(T)))) Unaligned {
     u32x4 v;
   };
-  // img2col mode only, per chunk: offset of the input pixel (image, oh*sh - ph, ow*sw - pw) of channel 0 that
-  // element 0 of the chunk reads at (kh, kw) = (0, 0) (may be negative), that pixel's row and column packed as
-  // two signed 16-bit fields, and how many of the chunk's positions are real (ow < OW and inside the matrix).
+  // ---- img2col mode --------------------------------------------------------------------------------------
+  // Stored row sr = k index (ic, kh, kw); a chunk = VEC consecutive output positions of one output row.  The load
+  // map gives a thread the same chunk column in every row it loads, so what depends on the positions is one set
+  // of values per thread, prepared by init(): the offset of the input pixel (image, oh*sh - ph, ow*sw - pw) of
+  // channel 0 that element 0 of the chunk reads at (kh, kw) = (0, 0) (may be negative), that pixel's row and
+  // column, and how many of the chunk's positions are real (ow < OW and inside the matrix).
+  int pofs, ih0, iw0, pcnt;
+  // A chunk is fetched in two phases so that the loads of all of a thread's chunks -- and the matrix-core work of
+  // the current tile -- overlap their latency: request_window() forms the address and issues the load(s),
+  // finish_window(), called when the tile is written to LDS, applies what depends on the loaded value.
   static constexpr int NP = (MODE == LD_IM2COL) ? NL : 1;
-  int pofs[NP];
-  int pxy[NP];
-  int pcnt[NP];
+  u32x4 win2[NP];  // stride 2: the second half of the window
+  u32x4 wmask[NP]; // the 16-byte mask that keeps elements [lo, hi)
+  int wstart[NP];  // element offset of the window
+  int winfo[NP];   // lo * (VEC + 1) + hi: elements [lo, hi) are kept; bit 8: the window leaves the tensor
+  int wsw;         // 2: windows are 2 * VEC elements of which the even ones are used; else 1
+  // LDS table of 16-byte masks: entry lo * (VEC + 1) + hi keeps elements [lo, hi) of a chunk
+  const unsigned char* masks;
+  static constexpr int MASK_ENTRIES = (VEC + 1) * (VEC + 1);
+  __device__ __forceinline__ void fill_masks(int tid, unsigned char* table) {
+    if (tid < MASK_ENTRIES) {
+      const int lo = tid / (VEC + 1), hi = tid % (VEC + 1);
+      u32x4 m;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (IS_F32) {
+          m[i] = (i >= lo && i < hi) ? 0xffffffffu : 0u;
+        } else {
+          m[i] = ((2 * i >= lo && 2 * i < hi) ? 0x0000ffffu : 0u) | ((2 * i + 1 >= lo && 2 * i + 1 < hi) ? 0xffff0000u : 0u);
+        }
+      }
+      *reinterpret_cast<u32x4*>(table + tid * 16) = m;
+    }
+    masks = table;
+  }
+
+  __device__ __forceinline__ u32x4 request_window(int q, int sr, int k0, const ConvGeom& g) {
+    const int kk = k0 + sr;
+    const int k = kofs + kk;
+    const int ic = g.d_khw.div(k), rem = k - ic * (g.KH * g.KW);
+    const int kh = g.d_kw.div(rem), kw = rem - kh * g.KW;
+    const int ih = ih0 + kh, iwf = iw0 + kw;  // input row, input column of element 0
+    const bool row_ok = kk < K && (unsigned)ih < (unsigned)g.H;
+    // (offsets of rows beyond K, which are masked, may wrap: unsigned arithmetic)
+    const int start = (int)((unsigned)pofs + ((unsigned)ic * (unsigned)g.H + (unsigned)kh) * (unsigned)g.W + (unsigned)kw);
+    if (g.sw <= 2 && g.numel_x >= 2 * VEC) {  // (a tensor smaller than the window has no valid window)
+      // Strides 1 and 2: element e is input pixel (ih, iwf + e * sw), so the chunk lies in one window of
+      // VEC * sw consecutive pixels.  Pixels left of the row (padding), right of it, and positions past the end
+      // of the output row read as zero: elements [lo, hi) are kept.  The window is loaded whole from an address
+      // that is always valid; no branch depends on a lane.
+      const int sw = g.sw, sft = sw - 1;
+      int lo = (sft - iwf) >> sft;            // ceil(-iwf / sw); <= 0 when the window starts inside the row
+      int hi = ((g.W - 1 - iwf) >> sft) + 1;  // elements up to the right edge of the row; <= 0 beyond it
+      lo = lo < 0 ? 0 : (lo > VEC ? VEC : lo);
+      hi = hi < 0 ? 0 : (hi > pcnt ? pcnt : hi);
+      if (!row_ok) hi = 0;
+      const bool any = hi > lo;
+      const bool inside = start >= 0 && start + VEC * sw <= g.numel_x;  // the whole window lies in the tensor
+      const T* win = src + ((any && inside) ? start : 0);
+      wstart[q] = start;
+      winfo[q] = (lo * (VEC + 1) + hi) | ((any && !inside) ? 0x100 : 0);
+      wmask[q] = *reinterpret_cast<const u32x4*>(masks + (lo * (VEC + 1) + hi) * 16);
+      wsw = sw;
+      if (sw == 2) win2[q] = reinterpret_cast<const Unaligned*>(win + VEC)->v;
+      return reinterpret_cast<const Unaligned*>(win)->v;
+    }
+    // Other strides: element e is input pixel (ih, iwf + e * sw), fetched one by one.
+    wstart[q] = 0;
+    winfo[q] = 0;
+    wmask[q] = u32x4{0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+    wsw = 1;
+    const int step = g.sw, W = g.W, cnt = row_ok ? pcnt : 0;
+    return gather_elements(start, step, [=](int e) { return e < cnt && (unsigned)(iwf + e * step) < (unsigned)W; });
+  }
+
+  // The rare forms of the gather (strides above 2, windows at the very ends of the tensor): a rolled loop of
+  // predicated single-element loads, small in code and registers because it is off the hot path.
+  template <class Pred>
+  __device__ __forceinline__ u32x4 gather_elements(int start, int step, Pred ok) const {
+    constexpr int HALF = VEC / 2, BITS = 8 * (int)sizeof(T);
+    unsigned long long h0 = 0, h1 = 0;
+#pragma unroll 1
+    for (int e = 0; e < VEC; ++e) {
+      if (ok(e)) {
+        const T x = src[start + e * step];
+        unsigned long long bits;
+        if constexpr (IS_F32)
+          bits = __builtin_bit_cast(unsigned int, x);
+        else
+          bits = __builtin_bit_cast(unsigned short, x);
+        bits <<= (e % HALF) * BITS;
+        if (e < HALF)
+          h0 |= bits;
+        else
+          h1 |= bits;
+      }
+    }
+    return u32x4{(unsigned int)h0, (unsigned int)(h0 >> 32), (unsigned int)h1, (unsigned int)(h1 >> 32)};
+  }
+
+  __device__ __forceinline__ u32x4 finish_window(int q, u32x4 v) const {
+    const int info = winfo[q];
+    if (wsw == 2) {
+      const u32x4 w = win2[q];
+      if constexpr (IS_F32) {
+        v = u32x4{v[0], v[2], w[0], w[2]};
+      } else {  // even 16-bit elements of the 16 loaded
+        v = u32x4{(v[0] & 0xffffu) | (v[1] << 16), (v[2] & 0xffffu) | (v[3] << 16),
+                  (w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] &= wmask[q][i];
+    if (info & 0x100) {
+      // first or last pixels of the tensor: the window would have left the allocation (it was read from a
+      // valid address instead and is replaced here, element by element)
+      const int lo = (info & 0xff) / (VEC + 1), hi = (info & 0xff) % (VEC + 1);
+      v = gather_elements(wstart[q], wsw, [=](int e) { return e >= lo && e < hi; });
+    }
+    return v;
+  }
 
   __device__ __forceinline__ void init(int tid, const ConvGeom& g) {
     if constexpr (MODE == LD_IM2COL) {
-#pragma unroll
-      for (int q = 0; q < NL; ++q) {
-        const tmap::Task t = LoadMap::task(tid, q);
-        const int sc = t.j * VEC;
-        const int p = r0 + sc;                       // GEMM column of element 0
-        const int r = g.d_owp.div(p), ow = p - r * g.OWP;  // r = image * OH + oh
-        const int img = g.d_oh.div(r), oh = r - img * g.OH;
-        const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
-        int cnt = g.OW - ow;
-        cnt = cnt < rows_left - sc ? cnt : rows_left - sc;
-        cnt = cnt < 0 ? 0 : (cnt > VEC ? VEC : cnt);
-        pcnt[q] = cnt;
-        // (a chunk with no real position may lie past the last image, where the offset would leave 32 bits)
-        pofs[q] = cnt > 0 ? (img * g.IC * g.H + ih0) * g.W + iw0 : 0;
-        pxy[q] = (ih0 & 0xffff) | (iw0 << 16);
-      }
+      static_assert(std::is_same<LoadMap, LoadMapRowMajor<SROWS, CPR, NT>>::value, "one chunk column per thread");
+      const int sc = LoadMap::task(tid, 0).j * VEC;
+      const int p = r0 + sc;                             // GEMM column of element 0
+      const int r = g.d_owp.div(p), ow = p - r * g.OWP;  // r = image * OH + oh
+      const int img = g.d_oh.div(r), oh = r - img * g.OH;
+      ih0 = oh * g.sh - g.ph;
+      iw0 = ow * g.sw - g.pw;
+      int cnt = g.OW - ow;
+      cnt = cnt < rows_left - sc ? cnt : rows_left - sc;
+      pcnt = cnt < 0 ? 0 : (cnt > VEC ? VEC : cnt);
+      // (a chunk with no real position may lie past the last image, where the offset would leave 32 bits)
+      pofs = pcnt > 0 ? (img * g.IC * g.H + ih0) * g.W + iw0 : 0;
     }
     if constexpr (MODE == LD_ELEM) {
 #pragma unroll
@@ -273,7 +317,7 @@ struct Operand {
   }
 
   // A K tile that lies entirely inside the matrix: no predicates at all in vector mode.
-  __device__ __forceinline__ void load_full(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
+  __device__ __forceinline__ void load_full(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) {
     if constexpr (MODE == LD_VEC) {
       const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
 #pragma unroll
@@ -303,7 +347,7 @@ struct Operand {
   }
 
   // The last, partial K tile (and every tile of the element-wise modes).
-  __device__ __forceinline__ void load_edge(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) const {
+  __device__ __forceinline__ void load_edge(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) {
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
@@ -314,6 +358,8 @@ struct Operand {
         u32x4 v = {0u, 0u, 0u, 0u};
         if (inside) v = *reinterpret_cast<const u32x4*>(base + off[q]);
         regs[q] = v;
+      } else if constexpr (MODE == LD_IM2COL) {
+        regs[q] = request_window(q, sr, k0, g);
       } else {
         regs[q] = gather(q, sr, sc, k0, g);
       }
@@ -325,16 +371,18 @@ struct Operand {
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
+      u32x4 v = regs[q];
+      if constexpr (MODE == LD_IM2COL) v = finish_window(q, v);
       if constexpr (!IS_F32) {
         const int swz = (LAYOUT == L_KC) ? swz_kc<CPR, MI>(t.i) : swz_mc<CPR, MI>(t.i);
-        *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = regs[q];
+        *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = v;
       } else if constexpr (LAYOUT == L_MC) {
-        *reinterpret_cast<u32x4*>(tile + (t.i * CPR + t.j) * 16) = regs[q];
+        *reinterpret_cast<u32x4*>(tile + (t.i * CPR + t.j) * 16) = v;
       } else {
         // fp32, KC source: row t.i, k = 4*t.j + e  ->  LDS [k][row]
         unsigned int* w = reinterpret_cast<unsigned int*>(tile);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[(t.j * 4 + e) * ROWS + t.i] = regs[q][e];
+        for (int e = 0; e < 4; ++e) w[(t.j * 4 + e) * ROWS + t.i] = v[e];
       }
     }
   }
