@@ -288,12 +288,15 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
 }
 
 // Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the tile
-// with the most workgroups.  Between tiles of one size the ring schedule and the 16x16 matrix-core shape are
-// preferred (they measure faster wherever both apply).  With slices > 1 only tiles that have a K-parallel
+// with the most workgroups.  Between tiles of one size the ring schedule, the 16x16 matrix-core shape and (small
+// tiles) the loads-ahead order are preferred (they measure faster wherever both apply).  With slices > 1 only tiles that have a K-parallel
 // form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
-  auto rank = [](const ConfigRow& r) { return (long long)r.bm * r.bn * 4 + (r.sched == 1 ? 2 : 0) + (r.mfma == 16 ? 1 : 0); };
+  auto rank = [](const ConfigRow& r) {
+    const int ahead = (r.sched == 2 && r.bm * r.bn <= 64 * 64) ? 1 : 0;  // measured faster on small tiles only
+    return (long long)r.bm * r.bn * 8 + (r.sched == 1 ? 4 : 0) + (r.mfma == 16 ? 2 : 0) + ahead;
+  };
   int best = -1, most = -1;
   long long most_blocks = -1;
   for (int c = 0; c < kNumConfigs; ++c) {

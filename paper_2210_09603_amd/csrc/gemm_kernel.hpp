@@ -30,7 +30,9 @@ namespace hidet {
 // ---------------------------------------------------------------------------------------------
 // The kernel, general schedule: two LDS stages, next tile staged through registers (the double
 // buffering of Section 3.1), fragments double-buffered in registers so that LDS reads of k step
-// ks+1 run under the MFMAs of k step ks.  Handles every load mode and every edge.
+// ks+1 run under the MFMAs of k step ks.  Handles every load mode and every edge.  Two orders of
+// the same steps: SCHED_SIMPLE issues the loads of the next tile at the top of an iteration,
+// SCHED_AHEAD one iteration earlier.
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
@@ -159,18 +161,78 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
     }
   };
 
+  // The same iteration with the loads one step further ahead (SCHED_AHEAD).  On entry the global loads of tile
+  // kt+1 (if there is one) are already in flight towards the staging registers: they were issued during the
+  // previous iteration, right after tile kt had been written to LDS and the registers were free again, and so
+  // have a whole iteration to arrive instead of the first k steps of one.  The staging registers stay occupied
+  // all the time, which is why this is a schedule of its own: it pays where an iteration is short (small tiles,
+  // latency-bound problems) and costs occupancy where the tile is large.
+  // `has_next`: there is a tile kt+1.  `ahead`: 1 = tile kt+2 lies entirely inside K (predicate-free loads),
+  // 2 = decide at run time whether there is a tile kt+2 and whether it is the partial one, 0 = there is none.
+  auto iteration_ahead = [&](int kt, auto has_next, auto ahead) {
+    unsigned char* cur = smem + (kt & 1) * Cfg::STAGE_BYTES;
+    unsigned char* nxt = smem + ((kt + 1) & 1) * Cfg::STAGE_BYTES;
+    auto stage_next = [&]() {
+      commit(nxt);
+      if constexpr (ahead.value == 1) {
+        opa.load_full(ra, tid, (kt + 2) * BK, p.g);
+        opb.load_full(rb, tid, (kt + 2) * BK, p.g);
+      } else if constexpr (ahead.value == 2) {
+        if (kt + 2 < KT) fetch(kt + 2);
+      }
+    };
+    if constexpr (KS % 2 == 0) {
+#pragma unroll
+      for (int ks = 0; ks + 1 < KS; ++ks) {
+        load_frags((ks + 1) & 1, cur, ks + 1);
+        if constexpr (has_next.value != 0) {
+          if (ks == KS - 2) stage_next();
+        }
+        mfmas(ks & 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (has_next.value != 0) {
+        __syncthreads();
+        load_frags(0, nxt, 0);
+      }
+      mfmas((KS - 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        load_frags(0, cur, ks);
+        mfmas(0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (has_next.value != 0) {
+        stage_next();
+        __syncthreads();
+      }
+    }
+  };
+
   if (KT > 0) {
+    using std::integral_constant;
     fetch(0);
     commit(smem);
+    if constexpr (Cfg::SCHED == SCHED_AHEAD) {
+      if (KT > 1) fetch(1);
+    }
     __syncthreads();
     if constexpr (KS % 2 == 0) load_frags(0, smem, 0);
     int kt = 0;
-    for (; kt + 1 < KT_full; ++kt) iteration(kt, std::integral_constant<int, 1>{});
-    if (kt + 1 < KT) {
-      iteration(kt, std::integral_constant<int, 2>{});
-      ++kt;
+    if constexpr (Cfg::SCHED == SCHED_AHEAD) {
+      for (; kt + 2 < KT_full; ++kt) iteration_ahead(kt, integral_constant<int, 1>{}, integral_constant<int, 1>{});
+      for (; kt + 1 < KT; ++kt) iteration_ahead(kt, integral_constant<int, 1>{}, integral_constant<int, 2>{});
+      iteration_ahead(kt, integral_constant<int, 0>{}, integral_constant<int, 0>{});
+    } else {
+      for (; kt + 1 < KT_full; ++kt) iteration(kt, integral_constant<int, 1>{});
+      if (kt + 1 < KT) {
+        iteration(kt, integral_constant<int, 2>{});
+        ++kt;
+      }
+      iteration(kt, integral_constant<int, 0>{});
     }
-    iteration(kt, std::integral_constant<int, 0>{});
     __syncthreads();  // the epilogue reuses the LDS
   }
 

@@ -9,7 +9,7 @@ namespace hidet {
 
 using LaunchFn = hipError_t (*)(const GemmParams&, hipStream_t);
 
-constexpr int kMaxConfigs = 32;
+constexpr int kMaxConfigs = 48;
 constexpr int kNumTypes = 3;     // index = hidet_dtype_t of the inputs: 0 f32, 1 f16, 2 bf16 (output has the same type)
 constexpr int kNumVariants = 20; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode;
                                  // +10: the same operand forms writing raw fp32 partial sums to a plain [M][N]
@@ -40,37 +40,39 @@ hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
 template <typename T, int BM, int BN, int BK, int WM, int WN, int MI, int TRANS_A, int SCHED>
 void register_config(Registry& r, int index, int type_index) {
   LaunchFn* v = r.fn[index][type_index];
+  // the operand forms that the ring schedule does not cover run the general kernel on the same tile
+  constexpr int GS = (SCHED == SCHED_PINGPONG) ? SCHED_SIMPLE : SCHED;
   // row-major A: KC;  row-major B: MC;  transposed B: KC;  transposed A: MC
   v[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-  v[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+  v[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
   v[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-  v[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+  v[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
   if constexpr (TRANS_A != 0) {
     v[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    v[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    v[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
     v[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    v[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    v[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
   }
   // convolution: weights are a row-major OC x (IC*KH*KW) matrix, B is the img2col gather, C is NCHW
-  v[conv_variant(0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_NCHW>>;
-  v[conv_variant(1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_NCHW>>;
+  v[conv_variant(0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_NCHW, GS>>;
+  v[conv_variant(1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_NCHW, GS>>;
   // K-parallel partial sums (fp32 out, plain map): built for the small and medium tiles, which are the ones a
   // problem with few output tiles and a long K wants, and for the ring-schedule tiles (medium-sized problems whose
   // tiles do not fill the device)
   if constexpr (BM * BN <= 128 * 128 || SCHED == SCHED_PINGPONG) {
     LaunchFn* w = v + kPartialVariants;
     w[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    w[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    w[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
     w[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    w[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+    w[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
     if constexpr (TRANS_A != 0) {
       w[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-      w[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+      w[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
       w[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-      w[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN>>;
+      w[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
     }
-    w[conv_variant(0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_PLAIN>>;
-    w[conv_variant(1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_PLAIN>>;
+    w[conv_variant(0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_PLAIN, GS>>;
+    w[conv_variant(1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_PLAIN, GS>>;
   }
 }
 
