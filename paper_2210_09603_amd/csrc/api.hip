@@ -486,6 +486,17 @@ hidet_status_t tune(const Problem& pr, const SplitK& sk, hipStream_t stream, int
   return HIDET_OK;
 }
 
+// No C++ exception crosses the C boundary: the cache and the tuner allocate host memory (strings, a map, a
+// vector), and a failed allocation is reported as a failed launch.
+template <class F>
+hidet_status_t guarded(F f) noexcept {
+  try {
+    return f();
+  } catch (...) {
+    return HIDET_ERR_LAUNCH;
+  }
+}
+
 // ---- task-mapping instances exposed to tests ----------------------------------------------------------
 struct TaskMapEntry {
   const char* expr;
@@ -534,7 +545,7 @@ hidet_status_t hidet_batched_gemm_cfg(int32_t config, int32_t in, int32_t out, i
                                         C, ldc, strideC, epi);
   if (st != HIDET_OK) return st;
   if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
-  return launch(pr, config, SplitK{}, (hipStream_t)stream);
+  return guarded([&] { return launch(pr, config, SplitK{}, (hipStream_t)stream); });
 }
 
 hidet_status_t hidet_gemm_cfg(int32_t config, int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M,
@@ -568,7 +579,7 @@ hidet_status_t hidet_conv2d_implicit_gemm_cfg(int32_t config, int32_t in, int32_
                                         y, epi);
   if (st != HIDET_OK) return st;
   if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
-  return launch(pr, config, SplitK{}, (hipStream_t)stream);
+  return guarded([&] { return launch(pr, config, SplitK{}, (hipStream_t)stream); });
 }
 
 hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
@@ -609,7 +620,7 @@ hidet_status_t hidet_tune_gemm(int32_t in, int32_t out, int32_t transA, int32_t 
   hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
                                         C, ldc, strideC, epi);
   if (st != HIDET_OK) return st;
-  return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us);
+  return guarded([&] { return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us); });
 }
 
 hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W, int64_t OC,
@@ -620,7 +631,7 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
   hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
                                         y, epi);
   if (st != HIDET_OK) return st;
-  return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us);
+  return guarded([&] { return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us); });
 }
 
 // ---- K-parallel ("split-K") forms ------------------------------------------------------------------------------
@@ -644,7 +655,7 @@ hidet_status_t hidet_batched_gemm_splitk(int32_t config, int32_t k_slices, int32
   sk.slices = k_slices <= 0 ? -1 : k_slices;
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
-  return launch(pr, config, sk, (hipStream_t)stream);
+  return guarded([&] { return launch(pr, config, sk, (hipStream_t)stream); });
 }
 
 hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int64_t Nb,
@@ -662,7 +673,7 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
   sk.slices = k_slices <= 0 ? -1 : k_slices;
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
-  return launch(pr, config, sk, (hipStream_t)stream);
+  return guarded([&] { return launch(pr, config, sk, (hipStream_t)stream); });
 }
 
 hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
@@ -678,7 +689,7 @@ hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, i
   SplitK sk;
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
-  return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us);
+  return guarded([&] { return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us); });
 }
 
 hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
@@ -695,7 +706,7 @@ hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int
   SplitK sk;
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
-  return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us);
+  return guarded([&] { return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us); });
 }
 
 int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity) {
@@ -726,11 +737,14 @@ hidet_status_t hidet_tune_load(const char* path) {
   if (!f) return HIDET_ERR_INVALID_ARG;
   char key[256];
   int cfg = 0, slices = 1;
-  std::lock_guard<std::mutex> lock(g_mutex);
-  while (std::fscanf(f, "%255s %d %d", key, &cfg, &slices) == 3)
-    if (cfg >= 0 && cfg < kNumConfigs && slices >= 1 && slices <= 1024) g_cache[std::string(key)] = Tuned{cfg, slices};
+  const hidet_status_t st = guarded([&] {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    while (std::fscanf(f, "%255s %d %d", key, &cfg, &slices) == 3)
+      if (cfg >= 0 && cfg < kNumConfigs && slices >= 1 && slices <= 1024) g_cache[std::string(key)] = Tuned{cfg, slices};
+    return HIDET_OK;
+  });
   std::fclose(f);
-  return HIDET_OK;
+  return st;
 }
 
 int32_t hidet_taskmap_count(void) { return kNumTaskMaps; }
