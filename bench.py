@@ -188,7 +188,8 @@ def side_report(torch, hb, wl, steps=200):
 def other_workload(torch, hb, wl, which, steps, warmup):
     """One of the secondary kernels on its own, K steps after W warm-up steps, so that a profiler sees nothing else:
     "softmax" = row softmax over the scores of the largest attention case (memory bound), "conv" = the case-study
-    convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced)."""
+    convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced), "conv64" = a
+    bottleneck convolution at batch 64 (throughput-sized, one kernel)."""
     import numpy as np
 
     def dev(stored):
@@ -203,6 +204,18 @@ def other_workload(torch, hb, wl, which, steps, warmup):
         name = "row softmax, f16, %d rows x %d columns (scores of attention batch*heads=192, seq=512), N(0,1)" % (b * s, s)
         unit_bytes = 2 * x.numel() * 2
         extra = {}
+    elif which == "conv64":
+        # a throughput-sized convolution: the 28x28, 128 -> 128, 3x3 bottleneck layer at batch 64 (single kernel)
+        c = wl.conv_case(6400, 64, 128, 28, 28, 128, 3, 3, 1, 1, "f16")
+        x, w, bias = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+        y = torch.empty((64, 128, c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+        sp = dict(stride=(1, 1), pad=(1, 1))
+        cfg, _ = hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=20, **sp)
+        step = lambda: hb.hidet_conv2d_implicit_gemm(x, w, y, config=cfg, epilogue=epi, **sp)
+        name = "conv2d 64x128x28x28 -> 128, 3x3, stride 1, pad 1, f16, bias + ReLU, He-init weights, seed 6400"
+        unit_bytes = (x.numel() + w.numel() + y.numel() + bias.numel()) * 2
+        extra = {"tile_config": cfg, "k_slices": 1, "flops": 2.0 * 64 * 128 * c["OH"] * c["OW"] * 128 * 9}
     else:
         c = wl.conv_case(6100, 1, 256, 28, 28, 256, 3, 3, 2, 1, "f16")
         x, w, bias = dev(c["x"]), dev(c["w"]), dev(c["bias"])
@@ -359,7 +372,7 @@ def main():
     ap.add_argument("--report", default=None, metavar="PATH",
                     help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
                          "and write the table to PATH as JSON; the headline line is printed as usual")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64"],
                     help="gemm (default): the headline benchmark; softmax / conv: one secondary kernel alone (for profiling)")
     ap.add_argument("--studies", default=None, metavar="PATH",
                     help="instead of the benchmark, run the schedule-space studies (latency of every schedule on the "
