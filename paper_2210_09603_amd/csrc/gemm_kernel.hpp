@@ -376,6 +376,134 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
 }
 
 // ---------------------------------------------------------------------------------------------
+// The large-tile schedule for operands whose rows are only element aligned (odd leading dimensions,
+// offset pointers -- the sizes on which input-centric schedule spaces have no schedule, Section 3.3).
+// Direct global -> LDS loads need aligned addresses, so here a stage travels through registers: it is
+// requested (16-byte loads at element alignment) during the memory phase of one iteration, written
+// into its ring slot during the memory phase of the next, and multiplied one iteration after that.
+// Phases, barriers and the half-stage offset between the two wavefronts of a SIMD are those of
+// gemm_kernel_pingpong; the waits are the compiler's (no hand-counted loads), except that a wave's LDS
+// writes and fragment reads must be complete before the barrier that ends its memory phase.
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong_regs(const GemmParams p) {
+  using T = typename Cfg::T;
+  using Acc = typename AccT<Cfg::MI>::type;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NT = Cfg::NT;
+  constexpr int FM = Cfg::FM, FN = Cfg::FN, KS = Cfg::KS;
+  static_assert(Cfg::NWAVES == 8 && !Cfg::IS_F32 && Cfg::MODE_A == LD_ELEM && Cfg::MODE_B == LD_ELEM && Cfg::STAGES == 4,
+                "ping-pong schedule through registers: 8 waves, 16-bit element mode, 4 LDS stages");
+  using OpA = Operand<T, BM, BK, Cfg::LA, LD_ELEM, NT, MI>;
+  using OpB = Operand<T, BN, BK, Cfg::LB, LD_ELEM, NT, MI>;
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem[Cfg::LDS_BYTES];
+
+  const int tid = threadIdx.x;
+  const int lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int grp = wave / 4;  // waves w and w+4 share a SIMD
+
+  const BlockCoords bc = block_coords<BM, BN>(p);
+  OpA opa;
+  OpB opb;
+  setup_operands<Cfg>(p, bc, opa, opb);
+  const tmap::Task wt = tmap::Spatial<Cfg::WAVES_M, Cfg::WAVES_N>::task(wave, 0);
+  const int wm0 = wt.i * Cfg::WTM, wn0 = wt.j * Cfg::WTN;
+
+  Acc acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < (int)(sizeof(Acc) / 4); ++r) acc[i][j][r] = 0.0f;
+
+  float col_bias[4];
+  load_col_bias<Cfg>(p, bc.n0 + wn0, lane, col_bias);
+
+  typename OpA::Frag fa[KS][FM];
+  typename OpB::Frag fb[KS][FN];
+  auto load_frags = [&](const unsigned char* stage) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa[ks][i] = opa.fragment(stage, lane, wm0, i, ks);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb[ks][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, ks);
+    }
+  };
+  auto mfmas = [&]() {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_op(fb[ks][j], fa[ks][i], acc[i][j]);
+  };
+  auto phase_barrier = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // all of this wave's LDS operations are complete (global loads may stay in flight)
+  auto lds_done = [&]() { __builtin_amdgcn_s_waitcnt(0xc07f); };
+
+  u32x4 ra[OpA::NL], rb[OpB::NL];
+  opa.init(tid, p.g);
+  opb.init(tid, p.g);
+  auto request = [&](int s) {  // global -> registers
+    opa.load_full(ra, tid, s * BK, p.g);
+    opb.load_full(rb, tid, s * BK, p.g);
+  };
+  auto deposit = [&](int s) {  // registers -> ring slot s % 4
+    unsigned char* slot = smem + (s & 3) * Cfg::STAGE_BYTES;
+    opa.store(ra, tid, slot);
+    opb.store(rb, tid, slot + Cfg::A_BYTES);
+  };
+
+  const int S = bc.k_len / BK;  // full stages
+  if (S > 0) {
+    request(0);
+    deposit(0);
+    if (S > 1) {
+      request(1);
+      deposit(1);
+    }
+    if (S > 2) request(2);
+    lds_done();
+    phase_barrier();
+    if (grp == 1) phase_barrier();
+    for (int s = 0; s < S; ++s) {
+      // ---- memory phase: stage s+1 (requested one iteration ago) into its slot, fragments of stage s, request s+2
+      if (s >= 1 && s + 1 < S) deposit(s + 1);
+      load_frags(smem + (s & 3) * Cfg::STAGE_BYTES);
+      if (s >= 1 && s + 2 < S) request(s + 2);
+      lds_done();
+      phase_barrier();
+      // ---- compute phase
+      __builtin_amdgcn_s_setprio(1);
+      mfmas();
+      __builtin_amdgcn_s_setprio(0);
+      phase_barrier();
+    }
+    if (grp == 0) phase_barrier();
+  }
+  if (S * BK < bc.k_len) {  // the partial last stage, zero filled
+    opa.load_edge(ra, tid, S * BK, p.g);
+    opb.load_edge(rb, tid, S * BK, p.g);
+    __syncthreads();
+    opa.store(ra, tid, smem);
+    opb.store(rb, tid, smem + Cfg::A_BYTES);
+    __syncthreads();
+    load_frags(smem);
+    mfmas();
+  }
+  __syncthreads();  // the epilogue reuses the LDS
+
+  epilogue<Cfg>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Parallel reduction on K, second pass (Sections 5.2 and 6.3.4: the matmul optimisation that lets
 // batch-1 convolutions fill the GPU): sums the fp32 partial results of the k_slices workgroups of
 // every output element and applies the fused epilogue.  p.A points at the workspace

@@ -29,7 +29,9 @@ constexpr int kPartialVariants = 10;  // offset of the K-parallel partial-sum ke
 
 template <class Cfg>
 hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
-  if constexpr (Cfg::SCHED == SCHED_PINGPONG)
+  if constexpr (Cfg::SCHED == SCHED_PINGPONG && Cfg::MODE_A == LD_ELEM)
+    hipLaunchKernelGGL(gemm_kernel_pingpong_regs<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
+  else if constexpr (Cfg::SCHED == SCHED_PINGPONG)
     hipLaunchKernelGGL(gemm_kernel_pingpong<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
   else
     hipLaunchKernelGGL(gemm_kernel<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
@@ -44,14 +46,14 @@ void register_config(Registry& r, int index, int type_index) {
   constexpr int GS = (SCHED == SCHED_PINGPONG) ? SCHED_SIMPLE : SCHED;
   // row-major A: KC;  row-major B: MC;  transposed B: KC;  transposed A: MC
   v[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-  v[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+  v[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
   v[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-  v[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+  v[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
   if constexpr (TRANS_A != 0) {
     v[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    v[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+    v[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
     v[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    v[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+    v[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
   }
   // convolution: weights are a row-major OC x (IC*KH*KW) matrix, B is the img2col gather, C is NCHW
   v[conv_variant(0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_NCHW, GS>>;
@@ -62,14 +64,14 @@ void register_config(Registry& r, int index, int type_index) {
   if constexpr (BM * BN <= 128 * 128 || SCHED == SCHED_PINGPONG) {
     LaunchFn* w = v + kPartialVariants;
     w[gemm_variant(0, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    w[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+    w[gemm_variant(0, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
     w[gemm_variant(0, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-    w[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+    w[gemm_variant(0, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
     if constexpr (TRANS_A != 0) {
       w[gemm_variant(1, 0, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-      w[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+      w[gemm_variant(1, 0, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_MC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
       w[gemm_variant(1, 1, 0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_VEC, LD_VEC, MAP_PLAIN, SCHED>>;
-      w[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, GS>>;
+      w[gemm_variant(1, 1, 1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_MC, L_KC, LD_ELEM, LD_ELEM, MAP_PLAIN, SCHED>>;
     }
     w[conv_variant(0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_PLAIN, GS>>;
     w[conv_variant(1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_PLAIN, GS>>;
