@@ -105,6 +105,29 @@ def test_every_config_on_an_odd_shape(dtype):
         assert err <= TOL[dtype], cfg
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_ring_schedules_every_stage_count(dtype):
+    """The ring schedules (direct global -> LDS loads on aligned operands, stages through registers on element-aligned
+    ones) fill and drain a ring of four stages: K values that give 0, 1, 2, 3, 4, 5 and 9 full stages, each with
+    and without a partial last stage, on every ring configuration."""
+    ring = [i for i in applicable_configs(dtype) if hb.hidet_config_info(i)["schedule"] == 1]
+    assert ring
+    for cfg in ring:
+        bk = hb.hidet_config_info(cfg)["block_k"]
+        for stages in (0, 1, 2, 3, 4, 5, 9):
+            for tail in (0, 8, 13):
+                K = stages * bk + tail
+                if K == 0:
+                    continue
+                aligned = tail % 8 == 0
+                M, N = (264, 520) if aligned else (263, 517)  # odd sizes: element-aligned rows
+                for tB in (False, True):
+                    c = wl.gemm_case(7450 + cfg, M, N, K, dtype, transB=tB, bias="col")
+                    err, _, ref = run_gemm_case(c, config=cfg, relu=True)
+                    assert within_bound(err, ref, dtype), (cfg, stages, tail, tB, err)
+    _say("ring configurations %s: all stage counts pass (%s)" % (ring, dtype))
+
+
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_every_config_conv(dtype):
     for cfg in applicable_configs(dtype):
