@@ -261,7 +261,7 @@ def studies(torch, hb, wl, steps=100):
     def tile(cfg):
         i = hb.hidet_config_info(cfg)
         return "%dx%dx%d/%dx%d/mfma%d/%s" % (i["block_m"], i["block_n"], i["block_k"], i["waves_m"], i["waves_n"], i["mfma"],
-                                            ("2stage", "ring", "2stage-ahead")[i["schedule"]])
+                                            ("2stage", "ring", "2stage-ahead", "2stage-ksplit")[i["schedule"]])
 
     out = {}
     ws = torch.empty(16 << 20, dtype=torch.float32, device="cuda")

@@ -159,7 +159,9 @@ typedef struct {
   int32_t is_f32;                    /* 1: configuration for fp32 inputs, 0: for fp16/bf16 inputs */
   int32_t schedule;                  /* 0: two LDS stages, next tile staged through registers;
                                         1: ring of four stages filled by direct global -> LDS loads, wavefront ping-pong;
-                                        2: as 0 with the loads of the next tile issued one iteration earlier */
+                                        2: as 0 with the loads of the next tile issued one iteration earlier;
+                                        3: as 2 with sixteen wavefronts, 16 / (waves_m * waves_n) groups that each
+                                           multiply a share of the k steps of every K tile (sums meet in LDS) */
   int32_t stages;                    /* LDS stages of block_k each */
   int32_t lds_bytes;                 /* LDS allocated by the workgroup */
 } hidet_config_info_t;

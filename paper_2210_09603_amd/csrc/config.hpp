@@ -19,7 +19,11 @@ struct GemmConfig {
   static constexpr int LA = LA_, LB = LB_, MODE_A = MODE_A_, MODE_B = MODE_B_, MAPPER = MAPPER_, SCHED = SCHED_;
   static constexpr bool IS_F32 = sizeof(T) == 4;
   static constexpr int VEC = 16 / (int)sizeof(T);
-  static constexpr int NWAVES = WAVES_M * WAVES_N;
+  // SCHED_KSPLIT: sixteen wavefronts, 16 / (WAVES_M x WAVES_N) groups of WAVES_M x WAVES_N that share every K tile,
+  // each multiplying its share of the k steps; their partial sums meet in LDS before the epilogue
+  static constexpr int NWAVES_MN = WAVES_M * WAVES_N;
+  static constexpr int WAVES_K = (SCHED == SCHED_KSPLIT) ? 16 / NWAVES_MN : 1;
+  static constexpr int NWAVES = NWAVES_MN * WAVES_K;
   static constexpr int NT = NWAVES * 64;
   static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
   static constexpr int FM = WTM / MI, FN = WTN / MI;            // MFMA tiles per wave: repeat(FM, FN)
@@ -31,15 +35,18 @@ struct GemmConfig {
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int STAGES = (SCHED == SCHED_PINGPONG) ? 4 : 2;
   // per-wave transposition regions of the epilogue: MI rows of the wave tile in fp32, rows padded by 16 bytes
-  static constexpr int EPI_BYTES = NWAVES * MI * (WTN * 4 + 16);
+  static constexpr int EPI_BYTES = NWAVES_MN * MI * (WTN * 4 + 16);
+  // partial accumulators of the wave groups 1 .. WAVES_K-1, behind the epilogue regions
+  static constexpr int RED_BYTES = (WAVES_K - 1) * NWAVES_MN * 64 * (FM * FN * MI * MI / 64) * 4;
   // img2col gather: table of the 16-byte masks that keep elements [lo, hi) of a chunk, behind the stages
   static constexpr int MASK_BYTES = (MODE_B == LD_IM2COL) ? (VEC + 1) * (VEC + 1) * 16 : 0;
   static constexpr int MAIN_BYTES = STAGES * STAGE_BYTES + MASK_BYTES;
-  static constexpr int LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  static constexpr int LDS_BYTES = MAIN_BYTES > EPI_BYTES + RED_BYTES ? MAIN_BYTES : EPI_BYTES + RED_BYTES;
   static constexpr int NL_A = BM * BK / VEC / NT;  // chunks per thread per tile
   static constexpr int NL_B = BN * BK / VEC / NT;
   static_assert(BM % (WAVES_M * MI) == 0 && BN % (WAVES_N * MI) == 0, "wave tiles must be whole MFMA tiles");
   static_assert(BK % KSTEP == 0, "BK must be a multiple of the MFMA k extent");
+  static_assert(KS % WAVES_K == 0, "the k steps of a tile must split evenly over the wave groups");
   static_assert(NL_A >= 1 && NL_B >= 1 && NL_A * NT * VEC == BM * BK && NL_B * NT * VEC == BN * BK,
                 "every thread must load the same whole number of chunks");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity of a gfx950 compute unit");

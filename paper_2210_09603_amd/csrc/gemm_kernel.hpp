@@ -39,7 +39,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   using T = typename Cfg::T;
   using Acc = typename AccT<Cfg::MI>::type;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NT = Cfg::NT;
-  constexpr int FM = Cfg::FM, FN = Cfg::FN, KS = Cfg::KS;
+  constexpr int FM = Cfg::FM, FN = Cfg::FN;
+  constexpr int KS = Cfg::KS / Cfg::WAVES_K;  // k steps of a tile that this wavefront multiplies
   using OpA = Operand<T, BM, BK, Cfg::LA, Cfg::MODE_A, NT, MI>;
   using OpB = Operand<T, BN, BK, Cfg::LB, Cfg::MODE_B, NT, MI>;
 
@@ -48,6 +49,9 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   const int tid = threadIdx.x;
   const int lane = tid % 64;
   const int wave = tid / 64;
+  const int kg = wave / Cfg::NWAVES_MN;   // wave group along K (always 0 unless SCHED_KSPLIT)
+  const int wsp = wave % Cfg::NWAVES_MN;  // position in the spatial(WAVES_M, WAVES_N) mapping
+  const int ks0 = kg * KS;                // first k step of every tile that this wavefront multiplies
 
   const BlockCoords bc = block_coords<BM, BN>(p);  // step 1
   OpA opa;
@@ -55,7 +59,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   setup_operands<Cfg>(p, bc, opa, opb);
 
   // step 4 (set-up): wave-level task mapping spatial(WAVES_M, WAVES_N) o repeat(FM, FN)
-  const tmap::Task wt = tmap::Spatial<Cfg::WAVES_M, Cfg::WAVES_N>::task(wave, 0);
+  const tmap::Task wt = tmap::Spatial<Cfg::WAVES_M, Cfg::WAVES_N>::task(wsp, 0);
   const int wm0 = wt.i * Cfg::WTM, wn0 = wt.j * Cfg::WTN;
 
   Acc acc[FM][FN];
@@ -97,9 +101,9 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   typename OpB::Frag fb[2][FN];
   auto load_frags = [&](int buf, const unsigned char* stage, int ks) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) fa[buf][i] = opa.fragment(stage, lane, wm0, i, ks);
+    for (int i = 0; i < FM; ++i) fa[buf][i] = opa.fragment(stage, lane, wm0, i, ks0 + ks);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) fb[buf][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, ks);
+    for (int j = 0; j < FN; ++j) fb[buf][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, ks0 + ks);
   };
   auto mfmas = [&](int buf) {
     // operands swapped on purpose: the accumulator tile then holds C transposed (see epilogue)
@@ -215,13 +219,13 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
     using std::integral_constant;
     fetch(0);
     commit(smem);
-    if constexpr (Cfg::SCHED == SCHED_AHEAD) {
+    if constexpr (Cfg::SCHED == SCHED_AHEAD || Cfg::SCHED == SCHED_KSPLIT) {
       if (KT > 1) fetch(1);
     }
     __syncthreads();
     if constexpr (KS % 2 == 0) load_frags(0, smem, 0);
     int kt = 0;
-    if constexpr (Cfg::SCHED == SCHED_AHEAD) {
+    if constexpr (Cfg::SCHED == SCHED_AHEAD || Cfg::SCHED == SCHED_KSPLIT) {
       for (; kt + 2 < KT_full; ++kt) iteration_ahead(kt, integral_constant<int, 1>{}, integral_constant<int, 1>{});
       for (; kt + 1 < KT; ++kt) iteration_ahead(kt, integral_constant<int, 1>{}, integral_constant<int, 2>{});
       iteration_ahead(kt, integral_constant<int, 0>{}, integral_constant<int, 0>{});
@@ -236,7 +240,33 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
     __syncthreads();  // the epilogue reuses the LDS
   }
 
-  epilogue<Cfg>(p, bc, wave, lane, wm0, wn0, acc, col_bias, smem);
+  if constexpr (Cfg::WAVES_K > 1) {
+    // the wave groups' partial sums meet in LDS (behind the epilogue regions); group 0 adds them in group order
+    constexpr int ACC = (int)(sizeof(Acc) / 4), PER_WAVE = 64 * FM * FN * ACC;
+    float* red = reinterpret_cast<float*>(smem + Cfg::EPI_BYTES);
+    if (kg > 0) {
+      float* mine = red + ((kg - 1) * Cfg::NWAVES_MN + wsp) * PER_WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < ACC; ++r) mine[((i * FN + j) * ACC + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (kg > 0) return;  // (no workgroup barrier follows)
+#pragma unroll
+    for (int g2 = 1; g2 < Cfg::WAVES_K; ++g2) {
+      const float* theirs = red + ((g2 - 1) * Cfg::NWAVES_MN + wsp) * PER_WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < ACC; ++r) acc[i][j][r] += theirs[((i * FN + j) * ACC + r) * 64];
+    }
+  }
+  epilogue<Cfg>(p, bc, wsp, lane, wm0, wn0, acc, col_bias, smem);
 }
 
 // ---------------------------------------------------------------------------------------------

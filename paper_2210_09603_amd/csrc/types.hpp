@@ -24,7 +24,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 enum : int { L_KC = 0, L_MC = 1 };                    // operand contiguity
 enum : int { LD_VEC = 0, LD_ELEM = 1, LD_IM2COL = 2 };  // how a chunk is fetched from global memory
 enum : int { MAP_PLAIN = 0, MAP_NCHW = 1 };           // output index map
-enum : int { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1, SCHED_AHEAD = 2 };  // main-loop schedule
+enum : int { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1, SCHED_AHEAD = 2, SCHED_KSPLIT = 3 };  // main-loop schedule
 
 // Division of a non-negative 31-bit integer by a divisor fixed at launch: floor(n / d) =
 // (n * mul) >> shift with mul = ceil(2^shift / d), shift = 31 + ceil(log2 d), which is exact for
