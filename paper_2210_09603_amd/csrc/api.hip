@@ -290,7 +290,7 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
 // Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the tile
 // with the most workgroups.  Between tiles of one size the ring schedule, the 16x16 matrix-core shape and (small
 // tiles) the loads-ahead order are preferred (they measure faster wherever both apply); the tiles that split K
-// over wave groups take part only when K spans at least two of their K tiles.  With slices > 1 only tiles that have a K-parallel
+// over wave groups take part only when K spans at least one of their K tiles.  With slices > 1 only tiles that have a K-parallel
 // form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
@@ -304,7 +304,7 @@ int default_config(const Problem& pr, int slices = 1) {
     if (!find_launcher(pr, c)) continue;
     if (slices > 1 && !find_partial_launcher(pr, c)) continue;
     const ConfigRow& r = kConfigs[c];
-    if (r.sched == 3 && pr.p.K < 2 * r.bk) continue;  // the wave groups along K need a K loop to share
+    if (r.sched == 3 && pr.p.K < r.bk) continue;  // the wave groups along K need at least one whole K tile to share
     const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch * (slices > 1 ? slices : 1);
     if (blocks >= 192 && (best < 0 || rank(r) > rank(kConfigs[best]))) best = c;
     if (blocks > most_blocks || (blocks == most_blocks && rank(r) > rank(kConfigs[most]))) {

@@ -40,7 +40,13 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   using Acc = typename AccT<Cfg::MI>::type;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NT = Cfg::NT;
   constexpr int FM = Cfg::FM, FN = Cfg::FN;
-  constexpr int KS = Cfg::KS / Cfg::WAVES_K;  // k steps of a tile that this wavefront multiplies
+  // k steps of a tile that this wavefront multiplies.  An fp32 MFMA covers only 2 or 4 values of k with one float per
+  // lane and operand, so fp32 fragments are read (and multiplied) G MFMAs at a time: a k step of the loop below is
+  // then G matrix-core k extents, and one LDS round trip feeds G times the matrix-core work.
+  constexpr int KS_MFMA = Cfg::KS / Cfg::WAVES_K;
+  // (Wave tiles of four or more MFMA tiles have enough matrix-core work per k extent to cover the round trip.)
+  constexpr int G = (!Cfg::IS_F32 || FM * FN > 2) ? 1 : (KS_MFMA % 4 == 0) ? 4 : (KS_MFMA % 2 == 0) ? 2 : 1;
+  constexpr int KS = KS_MFMA / G;
   using OpA = Operand<T, BM, BK, Cfg::LA, Cfg::MODE_A, NT, MI>;
   using OpB = Operand<T, BN, BK, Cfg::LB, Cfg::MODE_B, NT, MI>;
 
@@ -97,20 +103,25 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
     opa.store(ra, tid, stage);
     opb.store(rb, tid, stage + Cfg::A_BYTES);
   };
-  typename OpA::Frag fa[2][FM];
-  typename OpB::Frag fb[2][FN];
+  typename OpA::Frag fa[2][G][FM];
+  typename OpB::Frag fb[2][G][FN];
   auto load_frags = [&](int buf, const unsigned char* stage, int ks) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) fa[buf][i] = opa.fragment(stage, lane, wm0, i, ks0 + ks);
+    for (int g = 0; g < G; ++g) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) fb[buf][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, ks0 + ks);
+      for (int i = 0; i < FM; ++i) fa[buf][g][i] = opa.fragment(stage, lane, wm0, i, (ks0 + ks) * G + g);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb[buf][g][j] = opb.fragment(stage + Cfg::A_BYTES, lane, wn0, j, (ks0 + ks) * G + g);
+    }
   };
   auto mfmas = [&](int buf) {
     // operands swapped on purpose: the accumulator tile then holds C transposed (see epilogue)
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int j = 0; j < FN; ++j) acc[i][j] = mfma_op(fb[buf][j], fa[buf][i], acc[i][j]);
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_op(fb[buf][g][j], fa[buf][g][i], acc[i][j]);
   };
 
   // One iteration of the K loop.  `next`: 1 = tile kt+1 lies entirely inside K (predicate-free loads),
