@@ -297,7 +297,10 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
 // A last partial stage (K not a multiple of BK) is staged through registers with zero fill after the
 // ring has drained.
 // ---------------------------------------------------------------------------------------------
-template <class Cfg>
+// SLOTS = 2 is the same kernel for a K range of at most two stages: nothing is ever requested into a slot that was
+// used before, two slots of LDS are enough, and two such workgroups fit on a compute unit where the registers allow
+// (the output write of one then overlaps the loads and the matrix-core work of the other).
+template <class Cfg, int SLOTS = 4>
 __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams p) {
   using T = typename Cfg::T;
   using Acc = typename AccT<Cfg::MI>::type;
@@ -309,7 +312,9 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
   using OpB = Operand<T, BN, BK, Cfg::LB, LD_VEC, NT, MI>;
   constexpr int LOADS = OpA::NL + OpB::NL;  // direct loads per thread per stage
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[Cfg::LDS_BYTES];
+  static_assert(SLOTS == 4 || SLOTS == 2, "ring of four stages, or two stages without reuse");
+  constexpr int RING_BYTES = SLOTS * Cfg::STAGE_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[RING_BYTES > Cfg::EPI_BYTES ? RING_BYTES : Cfg::EPI_BYTES];
 
   const int tid = threadIdx.x;
   const int lane = tid % 64;
@@ -361,7 +366,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
   };
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;
   auto request = [&](int s) {  // direct loads of stage s into ring slot s % 4
-    const unsigned slot = smem_lds + (unsigned)((s & 3) * Cfg::STAGE_BYTES);
+    const unsigned slot = smem_lds + (unsigned)((s & (SLOTS - 1)) * Cfg::STAGE_BYTES);
     opa.load_direct(slot, wave, s * BK);
     opb.load_direct(slot + Cfg::A_BYTES, wave, s * BK);
   };
@@ -386,7 +391,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
     if (grp == 1) phase_barrier();
     for (int s = 0; s < S; ++s) {
       // ---- memory phase
-      load_frags(smem + (s & 3) * Cfg::STAGE_BYTES);
+      load_frags(smem + (s & (SLOTS - 1)) * Cfg::STAGE_BYTES);
       if (s + 3 < S) request(s + 3);
       wait_stage((s + 2 < S) + (s + 3 < S));
       phase_barrier();

@@ -31,9 +31,14 @@ template <class Cfg>
 hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
   if constexpr (Cfg::SCHED == SCHED_PINGPONG && Cfg::MODE_A == LD_ELEM)
     hipLaunchKernelGGL(gemm_kernel_pingpong_regs<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
-  else if constexpr (Cfg::SCHED == SCHED_PINGPONG)
-    hipLaunchKernelGGL(gemm_kernel_pingpong<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
-  else
+  else if constexpr (Cfg::SCHED == SCHED_PINGPONG) {
+    // a K range of at most two stages never reuses a ring slot: the two-slot form leaves LDS for a second workgroup
+    const int k_len = p.k_slices > 1 ? p.k_slice_len : p.K;
+    if (k_len <= 2 * Cfg::BK)
+      hipLaunchKernelGGL((gemm_kernel_pingpong<Cfg, 2>), dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
+    else
+      hipLaunchKernelGGL((gemm_kernel_pingpong<Cfg, 4>), dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
+  } else
     hipLaunchKernelGGL(gemm_kernel<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
   return hipGetLastError();
 }
