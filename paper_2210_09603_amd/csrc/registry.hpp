@@ -9,7 +9,7 @@ namespace hidet {
 
 using LaunchFn = hipError_t (*)(const GemmParams&, hipStream_t);
 
-constexpr int kMaxConfigs = 48;
+constexpr int kMaxConfigs = 64;
 constexpr int kNumTypes = 3;     // index = hidet_dtype_t of the inputs: 0 f32, 1 f16, 2 bf16 (output has the same type)
 constexpr int kNumVariants = 20; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode;
                                  // +10: the same operand forms writing raw fp32 partial sums to a plain [M][N]
