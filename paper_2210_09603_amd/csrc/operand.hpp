@@ -34,16 +34,14 @@ struct Operand {
   int r0;            // global row/column of the panel origin (needed by the img2col gather)
 
   // ---- global -> registers ------------------------------------------------------------------
-  __device__ __forceinline__ u32x4 gather(int q, int sr, int sc, int k0, const ConvGeom& g) const {
-    // Every load is issued unconditionally from a clamped (always valid) address and the predicate is
-    // applied to the value, so the VEC loads of a chunk are in flight together instead of waiting for one
-    // another behind branches.
+  // Element mode, a chunk of a partial K tile: rows are not 16-byte aligned (odd leading dimension, offset
+  // pointer).  A chunk that lies entirely inside the matrix is still fetched with one 16-byte load -- the address is
+  // only element aligned, which global loads accept on this target -- and only chunks that straddle an edge fall
+  // back to one load per element, each issued unconditionally from a clamped (always valid) address with the
+  // predicate applied to the value, so that they are in flight together instead of waiting behind branches.
+  __device__ __forceinline__ u32x4 gather(int sr, int sc, int k0) const {
     T tmp[VEC];
     {
-      // Element mode: rows are not 16-byte aligned (odd leading dimension, offset pointer).  A chunk that lies
-      // entirely inside the matrix is still fetched with one 16-byte load -- the address is only element
-      // aligned, which global loads accept on this target -- and only chunks that straddle an edge fall back
-      // to one predicated load per element.
       long long base;
       int valid;  // elements of the chunk inside the matrix
       bool whole;  // the 16 bytes of the chunk may be read at once
@@ -361,7 +359,7 @@ struct Operand {
       } else if constexpr (MODE == LD_IM2COL) {
         regs[q] = request_window(q, sr, k0, g);
       } else {
-        regs[q] = gather(q, sr, sc, k0, g);
+        regs[q] = gather(sr, sc, k0);
       }
     }
   }
