@@ -288,9 +288,12 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
 }
 
 // Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the tile
-// with the most workgroups.  Between tiles of one size the ring schedule, the 16x16 matrix-core shape and (small
+// with the most workgroups.  Outputs large enough to be bound by throughput rather than by one workgroup's
+// latency chain (at least 384 tiles of 64x64) ask for about two workgroups per compute unit instead, so that one
+// workgroup's loads and output write overlap another's arithmetic -- except from the ring schedule on a long K,
+// which overlaps them inside the workgroup.  Between tiles of one size the ring schedule, the 16x16 matrix-core shape and (small
 // tiles) the loads-ahead order are preferred (they measure faster wherever both apply); the tiles that split K
-// over wave groups take part only when K spans at least one of their K tiles.  With slices > 1 only tiles that have a K-parallel
+// over wave groups take part only when K spans at least one of their K tiles and the output is small.  With slices > 1 only tiles that have a K-parallel
 // form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
@@ -298,15 +301,32 @@ int default_config(const Problem& pr, int slices = 1) {
     const int ahead = (r.sched == 2 && r.bm * r.bn <= 64 * 64) ? 1 : 0;  // measured faster on small tiles only
     return (long long)r.bm * r.bn * 8 + (r.sched == 1 ? 4 : 0) + (r.mfma == 16 ? 2 : 0) + ahead;
   };
+  const bool throughput = ((M + 63) / 64) * ((N + 63) / 64) * pr.batch >= 384;
   int best = -1, most = -1;
-  long long most_blocks = -1;
+  long long most_blocks = -1, best_key = -(1LL << 62);
   for (int c = 0; c < kNumConfigs; ++c) {
     if (!find_launcher(pr, c)) continue;
     if (slices > 1 && !find_partial_launcher(pr, c)) continue;
     const ConfigRow& r = kConfigs[c];
-    if (r.sched == 3 && pr.p.K < r.bk) continue;  // the wave groups along K need at least one whole K tile to share
+    // the wave groups along K need at least one whole K tile to share, and are meant for latency-bound problems
+    if (r.sched == 3 && (pr.p.K < r.bk || throughput)) continue;
     const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch * (slices > 1 ? slices : 1);
-    if (blocks >= 192 && (best < 0 || rank(r) > rank(kConfigs[best]))) best = c;
+    // (the ring schedule proper runs GEMMs with 16-byte aligned operands only)
+    const bool ring = r.sched == 1 && pr.op == 0 && pr.elem_mode == 0 && pr.p.out_map == 0;
+    const long long enough = (throughput && !(ring && pr.p.K > 128)) ? 400 : 192;
+
+    // useful outputs per workgroup, discounted by the share of the tile that is padding, decide; then the smaller
+    // tile, then the schedule preferences
+    const long long area = (long long)r.bm * r.bn;
+    const long long useful = (M * N) / (((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn));
+    long long key = (useful * useful / area) * (1LL << 23) - area * 64 + (rank(r) & 63);
+    // a K of at most two stages runs the two-slot ring: two workgroups of a 256x128 tile share a compute unit and
+    // outrun one of a 256x256 tile
+    if (ring && pr.p.K <= 2 * r.bk && area == 256 * 128) key += (useful * useful / area) * (3LL << 22);
+    if (blocks >= enough && key > best_key) {
+      best = c;
+      best_key = key;
+    }
     if (blocks > most_blocks || (blocks == most_blocks && rank(r) > rank(kConfigs[most]))) {
       most_blocks = blocks;
       most = c;
