@@ -164,6 +164,8 @@ typedef struct {
                                            multiply a share of the k steps of every K tile (sums meet in LDS) */
   int32_t stages;                    /* LDS stages of block_k each */
   int32_t lds_bytes;                 /* LDS allocated by the workgroup */
+  int32_t waves_k;                   /* wave groups that share every K tile (1 except with schedule 3); the workgroup
+                                        has waves_m * waves_n * waves_k wavefronts */
 } hidet_config_info_t;
 int32_t hidet_config_count(void);
 hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info);

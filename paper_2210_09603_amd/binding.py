@@ -43,7 +43,7 @@ class hidet_epilogue_t(ctypes.Structure):
 
 class hidet_config_info_t(ctypes.Structure):
     _fields_ = [(n, _i32) for n in ("block_m", "block_n", "block_k", "waves_m", "waves_n", "mfma", "is_f32", "schedule",
-                                    "stages", "lds_bytes")]
+                                    "stages", "lds_bytes", "waves_k")]
 
 
 class HidetError(RuntimeError):

@@ -627,6 +627,7 @@ hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info) {
   info->is_f32 = r.is_f32;
   info->schedule = r.sched;
   info->stages = r.sched == 1 ? 4 : 2;
+  info->waves_k = r.sched == 3 ? 16 / (r.waves_m * r.waves_n) : 1;
   const int staging = info->stages * (r.bm + r.bn) * r.bk * (r.is_f32 ? 4 : 2);
   int epilogue = r.waves_m * r.mfma * (r.bn * 4 + 16 * r.waves_n);  // per-wave transposition regions
   if (r.sched == 3) epilogue += (16 / (r.waves_m * r.waves_n) - 1) * r.bm * r.bn * 4;  // partial sums of the wave groups along K

@@ -39,6 +39,7 @@ def test_version_and_schedule_space():
         assert c["mfma"] in (16, 32) and 1 <= waves <= 16
         assert c["block_m"] % (c["waves_m"] * c["mfma"]) == 0 and c["block_n"] % (c["waves_n"] * c["mfma"]) == 0
         assert c["lds_bytes"] <= 160 * 1024  # LDS of one compute unit
+        assert c["waves_k"] == (16 // waves if c["schedule"] == 3 else 1) and waves * c["waves_k"] <= 16
         # accumulators: one fp32 register per output element per lane, at most 256 of the 512 registers
         assert c["block_m"] * c["block_n"] // (waves * 64) <= 256
         key = tuple(c.values())
