@@ -209,6 +209,41 @@ __device__ __forceinline__ void load_col_bias(const GemmParams& p, int n_wave0, 
   }
 }
 
+// Wave groups along K (a tile configuration with WAVES_K > 1): every group holds partial sums of the same
+// BM x BN tile.  They meet in LDS behind the epilogue regions; group 0 adds them in group order (so the result
+// does not depend on timing) and is the only one to go on to the epilogue.  Contains one workgroup barrier and
+// must be entered after a barrier that ends all use of the staging buffers.  Returns false for the wavefronts
+// that are done.
+template <class Cfg, class Acc>
+__device__ __forceinline__ bool reduce_wave_groups(Acc (&acc)[Cfg::FM][Cfg::FN], unsigned char* smem, int kg, int wsp, int lane) {
+  if constexpr (Cfg::WAVES_K > 1) {
+    constexpr int FM = Cfg::FM, FN = Cfg::FN, ACC = (int)(sizeof(Acc) / 4), PER_WAVE = 64 * FM * FN * ACC;
+    float* red = reinterpret_cast<float*>(smem + Cfg::EPI_BYTES);
+    if (kg > 0) {
+      float* mine = red + ((kg - 1) * Cfg::NWAVES_MN + wsp) * PER_WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < ACC; ++r) mine[((i * FN + j) * ACC + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (kg > 0) return false;
+#pragma unroll
+    for (int g2 = 1; g2 < Cfg::WAVES_K; ++g2) {
+      const float* theirs = red + ((g2 - 1) * Cfg::NWAVES_MN + wsp) * PER_WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < ACC; ++r) acc[i][j][r] += theirs[((i * FN + j) * ACC + r) * 64];
+    }
+  }
+  return true;
+}
+
 // Step 5: fused epilogue + predicated store.  The MFMAs are issued with their operands swapped, so
 // an accumulator tile holds C transposed and each lane owns 4 consecutive columns of MI different
 // rows.  Storing that directly would scatter 8-byte pieces over as many cache lines, so each wave

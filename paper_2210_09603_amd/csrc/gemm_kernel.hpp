@@ -251,32 +251,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
     __syncthreads();  // the epilogue reuses the LDS
   }
 
-  if constexpr (Cfg::WAVES_K > 1) {
-    // the wave groups' partial sums meet in LDS (behind the epilogue regions); group 0 adds them in group order
-    constexpr int ACC = (int)(sizeof(Acc) / 4), PER_WAVE = 64 * FM * FN * ACC;
-    float* red = reinterpret_cast<float*>(smem + Cfg::EPI_BYTES);
-    if (kg > 0) {
-      float* mine = red + ((kg - 1) * Cfg::NWAVES_MN + wsp) * PER_WAVE + lane;
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int r = 0; r < ACC; ++r) mine[((i * FN + j) * ACC + r) * 64] = acc[i][j][r];
-    }
-    __syncthreads();
-    if (kg > 0) return;  // (no workgroup barrier follows)
-#pragma unroll
-    for (int g2 = 1; g2 < Cfg::WAVES_K; ++g2) {
-      const float* theirs = red + ((g2 - 1) * Cfg::NWAVES_MN + wsp) * PER_WAVE + lane;
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int r = 0; r < ACC; ++r) acc[i][j][r] += theirs[((i * FN + j) * ACC + r) * 64];
-    }
-  }
+  if (!reduce_wave_groups<Cfg>(acc, smem, kg, wsp, lane)) return;  // (no workgroup barrier follows)
   epilogue<Cfg>(p, bc, wsp, lane, wm0, wn0, acc, col_bias, smem);
 }
 
