@@ -189,7 +189,8 @@ def other_workload(torch, hb, wl, which, steps, warmup):
     """One of the secondary kernels on its own, K steps after W warm-up steps, so that a profiler sees nothing else:
     "softmax" = row softmax over the scores of the largest attention case (memory bound), "conv" = the case-study
     convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced), "conv64" = a
-    bottleneck convolution at batch 64 (throughput-sized, one kernel)."""
+    bottleneck convolution at batch 64 (throughput-sized, one kernel), "mlp" = the 128 x 768 x 3072 GEMM of the
+    transformer MLP (latency-bound, one kernel)."""
     import numpy as np
 
     def dev(stored):
@@ -204,6 +205,17 @@ def other_workload(torch, hb, wl, which, steps, warmup):
         name = "row softmax, f16, %d rows x %d columns (scores of attention batch*heads=192, seq=512), N(0,1)" % (b * s, s)
         unit_bytes = 2 * x.numel() * 2
         extra = {}
+    elif which == "mlp":
+        # the latency-bound GEMM of the transformer MLP: 128 x 768 x 3072 with a residual (few output tiles, long K)
+        c = wl.config2("f16")[1]
+        A, B, res = dev(c["A"]), dev(c["B"]), dev(c["residual"])
+        C = torch.empty((c["M"], c["N"]), dtype=torch.float16, device="cuda")
+        epi = hb.make_epilogue(residual=res)
+        cfg, _ = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=100)
+        step = lambda: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg)
+        name = "fused f16 GEMM C = A.B + residual, M=128, N=768, K=3072 (%s), seed %d" % (c["name"], c["seed"])
+        unit_bytes = (A.numel() + B.numel() + 2 * C.numel()) * 2
+        extra = {"tile_config": cfg, "k_slices": 1, "flops": 2.0 * c["M"] * c["N"] * c["K"]}
     elif which == "conv64":
         # a throughput-sized convolution: the 28x28, 128 -> 128, 3x3 bottleneck layer at batch 64 (single kernel)
         c = wl.conv_case(6400, 64, 128, 28, 28, 128, 3, 3, 1, 1, "f16")
@@ -372,7 +384,7 @@ def main():
     ap.add_argument("--report", default=None, metavar="PATH",
                     help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
                          "and write the table to PATH as JSON; the headline line is printed as usual")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64", "mlp"],
                     help="gemm (default): the headline benchmark; softmax / conv: one secondary kernel alone (for profiling)")
     ap.add_argument("--studies", default=None, metavar="PATH",
                     help="instead of the benchmark, run the schedule-space studies (latency of every schedule on the "
