@@ -185,7 +185,7 @@ def side_report(torch, hb, wl, steps=200):
     return rows
 
 
-def other_workload(torch, hb, wl, which, steps, warmup):
+def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False):
     """One of the secondary kernels on its own, K steps after W warm-up steps, so that a profiler sees nothing else:
     "softmax" = row softmax over the scores of the largest attention case (memory bound), "conv" = the case-study
     convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced), "conv64" = a
@@ -259,6 +259,10 @@ def other_workload(torch, hb, wl, which, steps, warmup):
                         "frac": round(gbps / 8000.0, 4), "traffic": None}}
     if "flops" in extra:
         out["config"]["TFLOPs"] = round(extra["flops"] / (ms * 1e-3) / 1e12, 2)
+    # Kernels of a few microseconds are launched more slowly from Python than they run: the same call replayed from a
+    # HIP graph gives the device-side time per call.
+    if graph_replay:
+        out["config"]["us_per_call_graph_replay"] = round(graph_time(torch, step), 2)
     return out
 
 
@@ -386,6 +390,9 @@ def main():
                          "and write the table to PATH as JSON; the headline line is printed as usual")
     ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64", "mlp"],
                     help="gemm (default): the headline benchmark; softmax / conv: one secondary kernel alone (for profiling)")
+    ap.add_argument("--graph-replay", action="store_true",
+                    help="with --workload other than gemm: also time the call replayed from a HIP graph "
+                         "(the device-side time of kernels shorter than a Python launch)")
     ap.add_argument("--studies", default=None, metavar="PATH",
                     help="instead of the benchmark, run the schedule-space studies (latency of every schedule on the "
                          "case-study convolution and on the headline GEMM; square sizes 2032..2048) and write them to PATH")
@@ -414,7 +421,7 @@ def main():
         return
 
     if args.workload != "gemm":
-        print(json.dumps(other_workload(torch, hb, wl, args.workload, args.steps, args.warmup)))
+        print(json.dumps(other_workload(torch, hb, wl, args.workload, args.steps, args.warmup, args.graph_replay)))
         return
 
     if args.copy_calibration > 0:
