@@ -95,7 +95,8 @@ typedef struct {
  * The tile configuration is the cached tuning winner for this problem if hidet_tune_gemm has
  * seen it, otherwise a size-based default.
  * Limits (HIDET_ERR_UNSUPPORTED beyond them): M, N and K are at most 2^31 - 65537 each; the number of
- * elements of A, B and C is not limited (offsets are 64-bit).
+ * elements of A, B and C may exceed 2^31 (offsets are 64-bit), but what an operand spans -- (rows - 1) * ld
+ * + cols elements per batch entry, batch * stride over the batch -- stays below 2^47 elements.
  */
 hidet_status_t hidet_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t M, int64_t N, int64_t K,
                           const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
@@ -121,8 +122,8 @@ hidet_status_t hidet_batched_gemm(int32_t in, int32_t out, int32_t transA, int32
  * be HIDET_BIAS_PER_ROW, i.e. one value per output channel, and residual (if any) is a dense
  * tensor of y's shape (ld_residual and batch_stride_residual are ignored).
  * Limits (HIDET_ERR_UNSUPPORTED beyond them): x has at most 2^31 - 65537 elements (y may have more),
- * H + 2*pad_h, W + 2*pad_w, KH and KW are at most 32767, and OC, Nb*OH*roundup(OW, 8) and IC*KH*KW are
- * at most 2^31 - 65537.
+ * H + 2*pad_h, W + 2*pad_w, KH, KW, stride_h and stride_w are at most 32767, and OC, Nb*OH*roundup(OW, 8)
+ * and IC*KH*KW are at most 2^31 - 65537.
  */
 hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
                                           int64_t OC, int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
@@ -211,7 +212,7 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
  *
  * Errors: HIDET_ERR_INVALID_ARG if the workspace is NULL or too small for the effective slice count,
  * HIDET_ERR_ALIGNMENT if it is misaligned, HIDET_ERR_UNSUPPORTED if batch > 65535 with slicing.
- * hidet_splitk_workspace_bytes returns -1 for negative sizes or k_slices < 1.
+ * hidet_splitk_workspace_bytes returns -1 for negative sizes, k_slices < 1 or a size beyond 2^62 bytes.
  */
 int64_t hidet_splitk_workspace_bytes(int64_t batch, int64_t M, int64_t N, int32_t k_slices);
 hidet_status_t hidet_batched_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int32_t transA,
@@ -261,6 +262,7 @@ hidet_status_t hidet_tune_load(const char* path);
  *   evaluated in fp32, y of the same dtype and shape with leading dimension ldy >= cols.  y == x
  *   (with ldy == ldx) is allowed; any other overlap is not.  A row of -inf only yields NaN.
  * Both: rows == 0 (softmax: or cols == 0) is an OK no-op; asynchronous on `stream`; no allocation.
+ * Limits (HIDET_ERR_UNSUPPORTED beyond them): cols is at most 2^31 - 65, rows * ld at most 2^47 elements.
  */
 typedef enum { HIDET_REDUCE_SUM = 0, HIDET_REDUCE_MAX = 1, HIDET_REDUCE_MEAN = 2 } hidet_reduce_op_t;
 hidet_status_t hidet_reduce_rows(int32_t in, int32_t out, int32_t op, int64_t rows, int64_t cols, const void* x,

@@ -81,6 +81,22 @@ constexpr long long kIntMax = 2147483647LL;
 // such indices in 32 bits and step past them by at most one tile (or one gather window) before comparing.
 constexpr long long kMaxDim = kIntMax - 65536;
 constexpr long long kMaxVecLd = 4LL << 20;  // in-tile element offsets (row * ld + col, row < 256) stay below 2^31
+// An operand spans (rows - 1) * ld + cols elements per batch entry and batch * stride over the batch; both are
+// kept below 2^47 (no allocation is larger), so that neither the checks here nor the 64-bit offsets of the kernels
+// can overflow.
+constexpr long long kMaxExtent = 1LL << 47;
+bool extent_ok(long long rows, long long ld, long long batch, long long stride) {
+  if (ld > kMaxExtent || stride > kMaxExtent) return false;
+  if (rows > 1 && ld > kMaxExtent / rows) return false;
+  if (batch > 1 && stride > kMaxExtent / batch) return false;
+  return true;
+}
+// a * b, saturating at 2^62 (a, b >= 0)
+long long sat_mul(long long a, long long b) {
+  constexpr long long lim = 1LL << 62;
+  if (a == 0 || b == 0) return 0;
+  return a > lim / b ? lim : a * b;
+}
 
 // GEMM: the output has the input type, or is fp32 for 16-bit inputs.  Convolution: same type only.
 hidet_status_t check_dtypes(int in, int out, bool conv) {
@@ -142,6 +158,9 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
     if (K > 0 && (!A || !B)) return HIDET_ERR_INVALID_ARG;
     if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return HIDET_ERR_INVALID_ARG;
     if (strideA < 0 || strideB < 0 || strideC < 0) return HIDET_ERR_INVALID_ARG;
+    if (!extent_ok(transA ? K : M, lda, batch, strideA) || !extent_ok(transB ? N : K, ldb, batch, strideB) ||
+        !extent_ok(M, ldc, batch, strideC))
+      return HIDET_ERR_UNSUPPORTED;
     if (batch > 1 && strideC < (M - 1) * ldc + N) return HIDET_ERR_INVALID_ARG;
     const bool head_split = epi && epi->out_map == HIDET_MAP_HEAD_SPLIT;
     if (head_split) {
@@ -152,6 +171,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
     if (epi && epi->residual && !head_split) {
       if (epi->ld_residual < N) return HIDET_ERR_INVALID_ARG;
       if (epi->batch_stride_residual < 0) return HIDET_ERR_INVALID_ARG;
+      if (!extent_ok(M, epi->ld_residual, batch, epi->batch_stride_residual)) return HIDET_ERR_UNSUPPORTED;
     }
     const size_t es = (size_t)elem_size(in);
     if (!aligned(A, es) || !aligned(B, es) || !aligned(C, (size_t)elem_size(out))) return HIDET_ERR_ALIGNMENT;
@@ -213,6 +233,10 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
     return HIDET_ERR_INVALID_ARG;
   st = check_epilogue(epi, out, true);
   if (st != HIDET_OK) return st;
+  // every factor is bounded before a product is formed (the products below then stay under 2^62)
+  if (Nb > kMaxDim || IC > kMaxDim || OC > kMaxDim || H > 32767 || W > 32767 || KH > 32767 || KW > 32767 ||
+      ph > 32767 || pw > 32767 || sh > 32767 || sw > 32767 || Nb * IC > kMaxDim)
+    return HIDET_ERR_UNSUPPORTED;
   const long long OH = (H + 2 * ph - KH) >= 0 ? (H + 2 * ph - KH) / sh + 1 : 0;
   const long long OW = (W + 2 * pw - KW) >= 0 ? (W + 2 * pw - KW) / sw + 1 : 0;
   // GEMM columns enumerate output positions with every output row padded to a multiple of 8 (see ConvGeom)
@@ -221,7 +245,7 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   // the gather keeps input rows and columns (padding included) in signed 16-bit fields and element
   // offsets in 32 bits
   if (M > kMaxDim || N > kMaxDim || K > kMaxDim || Nb * IC * H * W > kMaxDim || H + 2 * ph > 32767 ||
-      W + 2 * pw > 32767 || KH > 32767 || KW > 32767)
+      W + 2 * pw > 32767)
     return HIDET_ERR_UNSUPPORTED;
   const bool empty = (M == 0 || N == 0);
   if (!empty) {
@@ -279,8 +303,7 @@ LaunchFn find_launcher(const Problem& pr, int config) {
   return registry().fn[config][pr.dtype][(pr.wide_out ? kPartialVariants : 0) + variant];
 }
 
-// Size-based default when the problem has not been tuned: the largest tile that still yields at
-// least one workgroup per compute unit, else the configuration with the most workgroups.
+// The fp32-output kernel of a configuration: writes the partial sums of the K-parallel form.
 LaunchFn find_partial_launcher(const Problem& pr, int config) {
   if (config < 0 || config >= kNumConfigs) return nullptr;
   const int variant = pr.op == 1 ? conv_variant(pr.elem_mode) : gemm_variant(pr.transA, pr.transB, pr.elem_mode);
@@ -291,17 +314,17 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
 // with the most workgroups.  Outputs large enough to be bound by throughput rather than by one workgroup's
 // latency chain (at least 384 tiles of 64x64) ask for about two workgroups per compute unit instead, so that one
 // workgroup's loads and output write overlap another's arithmetic -- except from the ring schedule on a long K,
-// which overlaps them inside the workgroup.  Between tiles of one size the ring schedule, the 16x16 matrix-core shape and (small
-// tiles) the loads-ahead order are preferred (they measure faster wherever both apply); the tiles that split K
-// over wave groups take part only when K spans at least one of their K tiles and the output is small.  With slices > 1 only tiles that have a K-parallel
-// form take part.
+// which overlaps them inside the workgroup.  Between tiles of one size the ring schedule, the 16x16 matrix-core
+// shape and (small tiles) the loads-ahead order are preferred (they measure faster wherever both apply); the
+// tiles that split K over wave groups take part only when K spans at least one of their K tiles and the output
+// is small.  With slices > 1 only tiles that have a K-parallel form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
   auto rank = [](const ConfigRow& r) {
     const int ahead = (r.sched == 2 && r.bm * r.bn <= 64 * 64) ? 1 : 0;  // measured faster on small tiles only
     return (long long)r.bm * r.bn * 8 + (r.sched == 1 ? 4 : 0) + (r.mfma == 16 ? 2 : 0) + ahead;
   };
-  const bool throughput = ((M + 63) / 64) * ((N + 63) / 64) * pr.batch >= 384;
+  const bool throughput = sat_mul(((M + 63) / 64) * ((N + 63) / 64), pr.batch) >= 384;
   int best = -1, most = -1;
   long long most_blocks = -1, best_key = -(1LL << 62);
   for (int c = 0; c < kNumConfigs; ++c) {
@@ -310,7 +333,8 @@ int default_config(const Problem& pr, int slices = 1) {
     const ConfigRow& r = kConfigs[c];
     // the wave groups along K need at least one whole K tile to share, and are meant for latency-bound problems
     if (r.sched == 3 && (pr.p.K < r.bk || throughput)) continue;
-    const long long blocks = ((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn) * pr.batch * (slices > 1 ? slices : 1);
+    const long long blocks =
+        sat_mul(((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn), pr.batch * (slices > 1 ? slices : 1));
     // (the ring schedule proper runs GEMMs with 16-byte aligned operands only)
     const bool ring = r.sched == 1 && pr.op == 0 && pr.elem_mode == 0 && pr.p.out_map == 0;
     const long long enough = (throughput && !(ring && pr.p.K > 128)) ? 400 : 192;
@@ -408,7 +432,7 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
     actual = (p.K + len - 1) / len;
   }
   if (actual <= 1) {
-    const long long total = (long long)p.tiles_m * p.tiles_n * pr.batch;
+    const long long total = sat_mul((long long)p.tiles_m * p.tiles_n, pr.batch);
     if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
     p.total_blocks = (int)total;
     if (fn(p, stream) != hipSuccess) return HIDET_ERR_LAUNCH;
@@ -417,12 +441,12 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
   // ---- parallel reduction on K: partial sums into the workspace, then reduce + epilogue
   LaunchFn pfn = find_partial_launcher(pr, config);
   if (!pfn) return HIDET_ERR_NO_CONFIG;
-  const long long need = 4LL * pr.batch * actual * p.M * p.N;
+  if (pr.batch > 65535) return HIDET_ERR_UNSUPPORTED;
+  const long long total = sat_mul((long long)p.tiles_m * p.tiles_n, pr.batch * actual);
+  if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
+  const long long need = sat_mul(sat_mul(4LL * pr.batch * actual, p.M), p.N);
   if (!sk.workspace || sk.workspace_bytes < need) return HIDET_ERR_INVALID_ARG;
   if (!aligned(sk.workspace, 16)) return HIDET_ERR_ALIGNMENT;
-  if (pr.batch > 65535) return HIDET_ERR_UNSUPPORTED;
-  const long long total = (long long)p.tiles_m * p.tiles_n * pr.batch * actual;
-  if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
   GemmParams q = p;
   q.C = sk.workspace;
   q.ldc = p.N;
@@ -661,7 +685,8 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
 // ---- K-parallel ("split-K") forms ------------------------------------------------------------------------------
 int64_t hidet_splitk_workspace_bytes(int64_t batch, int64_t M, int64_t N, int32_t k_slices) {
   if (batch < 0 || M < 0 || N < 0 || k_slices < 1) return -1;
-  return 4 * batch * (int64_t)k_slices * M * N;
+  const long long bytes = sat_mul(sat_mul(sat_mul(4LL * k_slices, batch), M), N);
+  return bytes >= (1LL << 62) ? -1 : bytes;
 }
 
 hidet_status_t hidet_batched_gemm_splitk(int32_t config, int32_t k_slices, int32_t in, int32_t out, int32_t transA,
@@ -736,7 +761,8 @@ hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int
 int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity) {
   std::lock_guard<std::mutex> lock(g_mutex);
   const int n = (int)g_last_times.size();
-  for (int i = 0; i < n && i < capacity; ++i) us_per_config[i] = g_last_times[i];
+  if (us_per_config)
+    for (int i = 0; i < n && i < capacity; ++i) us_per_config[i] = g_last_times[i];
   return n;
 }
 

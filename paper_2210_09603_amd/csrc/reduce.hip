@@ -303,6 +303,12 @@ int elem_bytes(int dtype) { return dtype == HIDET_F32 ? 4 : 2; }
 
 }  // namespace
 
+// rows * ld elements must be addressable (below 2^47), so that the 64-bit row offsets cannot overflow
+static bool span_ok(long long rows, long long ld) {
+  constexpr long long lim = 1LL << 47;
+  return ld <= lim && (rows <= 1 || ld <= lim / rows);
+}
+
 extern "C" {
 
 hidet_status_t hidet_reduce_rows(int32_t in, int32_t out, int32_t op, int64_t rows, int64_t cols, const void* x,
@@ -313,6 +319,7 @@ hidet_status_t hidet_reduce_rows(int32_t in, int32_t out, int32_t op, int64_t ro
   if (cols > 0x7fffffffLL - 64) return HIDET_ERR_UNSUPPORTED;
   if (rows == 0) return HIDET_OK;
   if (!y || (cols > 0 && !x) || ldx < cols) return HIDET_ERR_INVALID_ARG;
+  if (!span_ok(rows, ldx)) return HIDET_ERR_UNSUPPORTED;
   if (!aligned_to(x, (size_t)elem_bytes(in)) || !aligned_to(y, (size_t)elem_bytes(out))) return HIDET_ERR_ALIGNMENT;
   RowParams p;
   p.x = x;
@@ -335,6 +342,7 @@ hidet_status_t hidet_softmax_rows(int32_t dtype, int64_t rows, int64_t cols, con
   if (cols > 0x7fffffffLL - 64) return HIDET_ERR_UNSUPPORTED;
   if (rows == 0 || cols == 0) return HIDET_OK;
   if (!x || !y || ldx < cols || ldy < cols) return HIDET_ERR_INVALID_ARG;
+  if (!span_ok(rows, ldx) || !span_ok(rows, ldy)) return HIDET_ERR_UNSUPPORTED;
   const size_t es = (size_t)elem_bytes(dtype);
   if (!aligned_to(x, es) || !aligned_to(y, es)) return HIDET_ERR_ALIGNMENT;
   RowParams p;

@@ -77,6 +77,10 @@ def test_gemm_argument_validation_happens_before_any_launch():
     assert _gemm(L, M=2 ** 31 - 65536, lda=8) == UNSUPPORTED
     assert _gemm(L, K=2 ** 31 - 65536, lda=2 ** 31, ldb=8) == UNSUPPORTED
     assert _gemm(L, N=2 ** 31 - 65536, ldb=2 ** 31, ldc=2 ** 31) == UNSUPPORTED
+    # what an operand spans stays below 2^47 elements, so that no offset (and no check) can overflow 64 bits
+    assert _gemm(L, lda=2 ** 62) == UNSUPPORTED
+    assert _gemm(L, M=2 ** 20, lda=2 ** 28) == UNSUPPORTED
+    assert _gemm(L, ldc=2 ** 61) == UNSUPPORTED
     assert _gemm(L, A=0x1001) == ALIGN
     assert _gemm(L, i=hb.HIDET_F32, o=hb.HIDET_F32, C=0x3002) == ALIGN
     assert _gemm(L, config=10 ** 6) == NOCFG
@@ -128,6 +132,11 @@ def test_batched_and_conv_argument_validation():
     assert L.hidet_batched_gemm(f16, f16, 0, 0, 4, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 32, None, None) == 1
     assert L.hidet_batched_gemm(f16, f16, 0, 0, -1, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 64, None, None) == 1
     assert L.hidet_batched_gemm(f16, f16, 0, 0, 0, 8, 8, 8, None, 8, 64, None, 8, 64, None, 8, 64, None, None) == 0
+    # batch * stride beyond 2^47 elements
+    assert L.hidet_batched_gemm(f16, f16, 0, 0, 2 ** 20, 8, 8, 8, 0x1000, 8, 2 ** 30, 0x2000, 8, 64, 0x3000, 8, 64, None,
+                                None) == 2
+    assert L.hidet_batched_gemm(f16, f16, 0, 0, 4, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 2 ** 62, None,
+                                None) == 2
     conv = lambda **k: L.hidet_conv2d_implicit_gemm(
         k.get("i", f16), k.get("o", f16), k.get("Nb", 1), k.get("IC", 4), k.get("H", 8), k.get("W", 8), k.get("OC", 4),
         k.get("KH", 3), k.get("KW", 3), k.get("sh", 1), k.get("sw", 1), k.get("ph", 1), k.get("pw", 1), k.get("x", 0x1000),
@@ -150,6 +159,10 @@ def test_batched_and_conv_argument_validation():
     assert conv(epi=ctypes.byref(e)) == 1
     assert conv(H=40000) == 2 and conv(pw=20000) == 2  # rows/columns are kept in 16-bit fields
     assert conv(IC=331, H=14322, W=453) == 2  # x has 2^31 - 2 elements: a gather window could step past 2^31
+    # every factor is bounded before products are formed: none of these may wrap into an accepted geometry
+    assert conv(sh=2 ** 32 + 1) == 2 and conv(sw=2 ** 40) == 2 and conv(ph=2 ** 62) == 2
+    assert conv(Nb=2 ** 33, IC=2 ** 31) == 2 and conv(Nb=2 ** 62) == 2 and conv(OC=2 ** 40) == 2
+    assert conv(KH=2 ** 32 + 3, H=8) == 2
     assert hb.lib().hidet_status_string(3) == b"misaligned pointer"
 
 
@@ -161,6 +174,9 @@ def test_splitk_argument_validation():
     assert L.hidet_splitk_workspace_bytes(1, 64, 64, 1) == 4 * 64 * 64
     assert L.hidet_splitk_workspace_bytes(1, 64, 64, 0) == -1
     assert L.hidet_splitk_workspace_bytes(-1, 64, 64, 2) == -1
+    assert L.hidet_splitk_workspace_bytes(2 ** 31, 2 ** 31, 2 ** 31, 16) == -1  # beyond 64 bits
+    assert L.hidet_splitk_workspace_bytes(1, 2 ** 30, 2 ** 20, 2) == 8 * 2 ** 50
+    assert L.hidet_tune_last_times(None, 4) >= 0  # a null buffer only asks for the count
     sliceable = [i for i in range(hb.hidet_config_count())
                  if not hb.hidet_config_info(i)["is_f32"]
                  and hb.hidet_config_info(i)["block_m"] * hb.hidet_config_info(i)["block_n"] <= 128 * 128
@@ -231,6 +247,7 @@ def test_reduction_argument_validation():
                                           k.get("ldx", 8), k.get("y", 0x2000), k.get("ldy", 8), None)
     assert sm(x=None) == 1 and sm(y=None) == 1 and sm(ldx=7) == 1 and sm(ldy=7) == 1 and sm(cols=-1) == 1 and sm(t=3) == 1
     assert sm(y=0x2001) == 3 and sm(cols=2 ** 31) == 2
+    assert sm(rows=2 ** 40, ldx=2 ** 20, ldy=2 ** 20) == 2 and sm(ldy=2 ** 62) == 2 and red(rows=2 ** 50, ldx=2 ** 10) == 2
     assert sm(rows=0, x=None, y=None) == 0 and sm(cols=0, ldx=0, ldy=0, x=None, y=None) == 0
 
 
