@@ -190,7 +190,8 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False):
     "softmax" = row softmax over the scores of the largest attention case (memory bound), "conv" = the case-study
     convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced), "conv64" = a
     bottleneck convolution at batch 64 (throughput-sized, one kernel), "mlp" = the 128 x 768 x 3072 GEMM of the
-    transformer MLP (latency-bound, one kernel)."""
+    transformer MLP (latency-bound, one kernel), "gemm32" = the headline shape in fp32 (bound by the fp32
+    matrix-core rate)."""
     import numpy as np
 
     def dev(stored):
@@ -216,6 +217,17 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False):
         name = "fused f16 GEMM C = A.B + residual, M=128, N=768, K=3072 (%s), seed %d" % (c["name"], c["seed"])
         unit_bytes = (A.numel() + B.numel() + 2 * C.numel()) * 2
         extra = {"tile_config": cfg, "k_slices": 1, "flops": 2.0 * c["M"] * c["N"] * c["K"]}
+    elif which == "gemm32":
+        # the headline shape in fp32: bound by the fp32 matrix-core rate (157.3 TFLOP/s), not by memory
+        c = wl.gemm_case(5200, 4096, 4096, 4096, "f32", bias="col")
+        A, B, bias = dev(c["A"]), dev(c["B"]), dev(c["bias"])
+        C = torch.empty((4096, 4096), dtype=torch.float32, device="cuda")
+        epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True)
+        cfg, _ = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=5)
+        step = lambda: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg)
+        name = "fused f32 GEMM C = ReLU(A.B + bias), M=N=K=4096, U(-1,1), seed 5200"
+        unit_bytes = (A.numel() + B.numel() + C.numel() + bias.numel()) * 4
+        extra = {"tile_config": cfg, "k_slices": 1, "flops": 2.0 * 4096 ** 3}
     elif which == "conv64":
         # a throughput-sized convolution: the 28x28, 128 -> 128, 3x3 bottleneck layer at batch 64 (single kernel)
         c = wl.conv_case(6400, 64, 128, 28, 28, 128, 3, 3, 1, 1, "f16")
@@ -259,6 +271,11 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False):
                         "frac": round(gbps / 8000.0, 4), "traffic": None}}
     if "flops" in extra:
         out["config"]["TFLOPs"] = round(extra["flops"] / (ms * 1e-3) / 1e12, 2)
+    if which == "gemm32":
+        tf = extra["flops"] / (ms * 1e-3) / 1e12
+        out.update(metric="TFLOP/s of one secondary kernel, 1 GPU", value=round(tf, 2), unit="TFLOP/s", dtype="f32")
+        out["roofline"] = {"bound": "mfma", "achieved": round(tf, 2), "peak": 157.3, "unit": "TFLOP/s",
+                           "frac": round(tf / 157.3, 4), "traffic": None}
     # Kernels of a few microseconds are launched more slowly from Python than they run: the same call replayed from a
     # HIP graph gives the device-side time per call.
     if graph_replay:
@@ -388,7 +405,7 @@ def main():
     ap.add_argument("--report", default=None, metavar="PATH",
                     help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
                          "and write the table to PATH as JSON; the headline line is printed as usual")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64", "mlp"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64", "mlp", "gemm32"],
                     help="gemm (default): the headline benchmark; softmax / conv: one secondary kernel alone (for profiling)")
     ap.add_argument("--graph-replay", action="store_true",
                     help="with --workload other than gemm: also time the call replayed from a HIP graph "
