@@ -137,7 +137,9 @@ def side_report(torch, hb, wl, steps=200):
                                 lambda: hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=steps, **sp), y.numel())
         flops = 2.0 * c["Nb"] * c["OC"] * c["OH"] * c["OW"] * c["IC"] * c["KH"] * c["KW"]
         nbytes = (x.numel() + w.numel() + y.numel()) * 2
-        uc = cold(lambda x_, w_, y_: hb.hidet_conv2d_implicit_gemm(x_, w_, y_, epilogue=epi, config=cfg, **sp), [x, w, y], nbytes)
+        # (no configuration named: the call runs what the tuner remembered, which for the 1x1 layers may be the
+        # batched-GEMM form)
+        uc = cold(lambda x_, w_, y_: hb.hidet_conv2d_implicit_gemm(x_, w_, y_, epilogue=epi, **sp), [x, w, y], nbytes)
         add(c["name"], "f16", flops, nbytes, us, cfg, ts, sl, uc)
     for c in wl.config4("f16"):
         Q, Kt, V, S = (dev(c[k], "f16") for k in ("Q", "K", "V", "S"))
@@ -363,14 +365,16 @@ def studies(torch, hb, wl, steps=100):
         y = torch.empty((c["Nb"], c["OC"], c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
         sp = dict(stride=(c["stride"], c["stride"]), pad=(c["pad"], c["pad"]))
         epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
-        cfg, _ = hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp)
+        # both anchors tuned; no configuration named, so each call runs what the tuner remembered for it
+        hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=steps, **sp)
+        hb.hidet_tune_conv2d(x, w, y, iters=steps, **sp)
         bias4 = b.view(1, -1, 1, 1)
 
         def unfused():
-            hb.hidet_conv2d_implicit_gemm(x, w, y, config=cfg, **sp)
+            hb.hidet_conv2d_implicit_gemm(x, w, y, **sp)
             y.add_(bias4)
             y.relu_()
-        fused_us = graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, config=cfg, **sp))
+        fused_us = graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, **sp))
         fusion.append({"workload": c["name"], "fused_us": round(fused_us, 2), "unfused_3_kernels_us": round(graph_time(torch, unfused), 2)})
     for c in wl.config2("f16"):
         A, B, bias = dev(c["A"]), dev(c["B"]), dev(c["bias"])
@@ -390,6 +394,31 @@ def studies(torch, hb, wl, steps=100):
         fused_us = graph_time(torch, lambda: hb.hidet_gemm(A, B, C, epilogue=epi, config=cfg))
         fusion.append({"workload": c["name"], "fused_us": round(fused_us, 2), "unfused_us": round(graph_time(torch, unfused), 2)})
     out["fused_vs_separate_elementwise_kernels_f16"] = fusion
+
+    # 1x1 convolutions (two thirds of the bottleneck network's layers): the gather form against the batched-GEMM form
+    # that a call without an explicit configuration takes; best configuration of each form, HIP-graph replays
+    pointwise = []
+    hb.hidet_tune_clear()
+    for nb in (1, 64):
+        for IC, OC, HW in ((64, 256, 56), (256, 64, 56), (128, 512, 28), (512, 128, 28), (256, 1024, 14), (1024, 256, 14),
+                           (512, 2048, 7), (2048, 512, 7)):
+            c = wl.conv_case(6500 + nb + HW, nb, IC, HW, HW, OC, 1, 1, 1, 0, "f16")
+            x, w, b = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+            y = torch.empty((nb, OC, HW, HW), dtype=torch.float16, device="cuda")
+            epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+            untuned = graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi))
+            gather = min((graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm(x, w, y, epilogue=epi, config=i), 10, 5), i)
+                         for i in range(hb.hidet_config_count()) if not hb.hidet_config_info(i)["is_f32"])
+            A, B, C = w.view(1, OC, IC).expand(nb, OC, IC), x.view(nb, IC, HW * HW), y.view(nb, OC, HW * HW)
+            g_cfg, _ = hb.hidet_tune_gemm(A, B, C, epilogue=epi, iters=steps if nb == 1 else 20)
+            gemm_form = graph_time(torch, lambda: hb.hidet_batched_gemm(A, B, C, epilogue=epi, config=g_cfg))
+            flops = 2.0 * nb * OC * IC * HW * HW
+            pointwise.append({"layer": "%dx%d %d->%d k1" % (HW, HW, IC, OC), "batch": nb,
+                              "gather_form_us": round(gather[0], 2), "gather_form_tile": tile(gather[1]),
+                              "gemm_form_us": round(gemm_form, 2), "gemm_form_tile": tile(g_cfg),
+                              "untuned_call_us": round(untuned, 2),
+                              "TFLOPs_best": round(flops / min(gather[0], gemm_form) * 1e-6, 2)})
+    out["pointwise_conv_forms_f16"] = pointwise
     return out
 
 

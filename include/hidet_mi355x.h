@@ -121,6 +121,11 @@ hidet_status_t hidet_batched_gemm(int32_t in, int32_t out, int32_t transA, int32
  * fused epilogue, so no img2col matrix is ever materialised.  In the epilogue, bias (if any) must
  * be HIDET_BIAS_PER_ROW, i.e. one value per output channel, and residual (if any) is a dense
  * tensor of y's shape (ld_residual and batch_stride_residual are ignored).
+ * A 1x1 convolution with unit stride and no padding needs no gather (image b of x already is the IC x H*W
+ * row-major matrix of the GEMM): without an explicit configuration it runs as the batched GEMM
+ * y[b] = w . x[b], weights shared across the batch, unless hidet_tune_conv2d measured the gather form to be
+ * faster for this problem; a call with an explicit configuration always runs the gather form.  The results of
+ * the two forms agree to rounding (different summation order).
  * Limits (HIDET_ERR_UNSUPPORTED beyond them): x has at most 2^31 - 65537 elements (y may have more),
  * H + 2*pad_h, W + 2*pad_w, KH, KW, stride_h and stride_w are at most 32767, and OC, Nb*OH*roundup(OW, 8)
  * and IC*KH*KW are at most 2^31 - 65537.
@@ -177,6 +182,9 @@ hidet_status_t hidet_config_info(int32_t config, hidet_config_info_t* info);
  * time `iters` launches of each with HIP events on `stream`, remember the fastest under a key made
  * of (operation, dtypes, transposes, sizes, epilogue kind) and report it.  The output buffer is
  * overwritten with valid results.  best_config / best_us may be NULL.  Synchronises `stream`.
+ * For a 1x1 convolution with unit stride and no padding both forms (gather, batched GEMM) are enumerated and
+ * the faster one is remembered; the reported configuration may then belong to the batched-GEMM form, which
+ * only a call without an explicit configuration runs.
  */
 hidet_status_t hidet_tune_gemm(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
                                int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,

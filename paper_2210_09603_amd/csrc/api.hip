@@ -364,6 +364,7 @@ std::mutex g_mutex;
 struct Tuned {
   int config;
   int slices;
+  int route = 0;  // convolutions only: 1 = the remembered choice is for the batched-GEMM form of a 1x1 convolution
 };
 std::map<std::string, Tuned> g_cache;
 std::vector<float> g_last_times;
@@ -523,7 +524,7 @@ hidet_status_t tune(const Problem& pr, const SplitK& sk, hipStream_t stream, int
   }
   {
     std::lock_guard<std::mutex> lock(g_mutex);
-    if (best >= 0) g_cache[problem_key(pr, sk.workspace != nullptr)] = Tuned{best, best_sl};
+    if (best >= 0) g_cache[problem_key(pr, sk.workspace != nullptr)] = Tuned{best, best_sl, 0};
     g_last_times = times;
   }
   if (best_config) *best_config = best;
@@ -541,6 +542,86 @@ hidet_status_t guarded(F f) noexcept {
   } catch (...) {
     return HIDET_ERR_LAUNCH;
   }
+}
+
+// ---- convolution calls ------------------------------------------------------------------------------------------
+// A 1x1 convolution with unit stride and no padding needs no gather: image b of x is an IC x (H*W) row-major
+// matrix as it stands, so y[b] = w . x[b] is a batched GEMM with the weights shared across the batch (and the
+// aligned direct-to-LDS loads of the ring schedule apply).  Such a call carries both descriptions of the problem.
+struct ConvCall {
+  Problem conv, gemm;
+  bool pointwise = false;
+};
+
+hidet_status_t make_conv_call(ConvCall& cc, int in, int out, long long Nb, long long IC, long long H, long long W,
+                              long long OC, long long KH, long long KW, long long sh, long long sw, long long ph,
+                              long long pw, const void* x, const void* w, void* y, const hidet_epilogue_t* epi) {
+  const hidet_status_t st = make_conv_problem(cc.conv, in, out, Nb, IC, H, W, OC, KH, KW, sh, sw, ph, pw, x, w, y, epi);
+  if (st != HIDET_OK) return st;
+  cc.pointwise = false;
+  if (KH == 1 && KW == 1 && sh == 1 && sw == 1 && ph == 0 && pw == 0) {
+    hidet_epilogue_t e;
+    const hidet_epilogue_t* ep = nullptr;
+    if (epi) {  // the residual is a dense tensor of y's shape
+      e = *epi;
+      e.ld_residual = H * W;
+      e.batch_stride_residual = OC * H * W;
+      ep = &e;
+    }
+    cc.pointwise = make_gemm_problem(cc.gemm, in, out, 0, 0, Nb, OC, H * W, IC, w, IC, 0, x, H * W, IC * H * W, y, H * W,
+                                     OC * H * W, ep) == HIDET_OK;
+  }
+  return HIDET_OK;
+}
+
+// An explicit configuration always runs the gather form; config < 0 runs what the tuner remembered for this
+// convolution, else (1x1 convolutions) the batched-GEMM form with its size-based default.
+hidet_status_t launch_conv(const ConvCall& cc, int config, const SplitK& sk, hipStream_t stream) {
+  if (config >= 0 || !cc.pointwise) return launch(cc.conv, config, sk, stream);
+  Tuned t{-1, 1, 0};
+  {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    auto it = g_cache.find(problem_key(cc.conv, sk.workspace != nullptr));
+    if (it != g_cache.end()) t = it->second;
+  }
+  if (t.config < 0) return launch(cc.gemm, -1, sk, stream);
+  SplitK one = sk;
+  if (one.slices < 0) one.slices = t.slices;
+  return launch(t.route == 1 ? cc.gemm : cc.conv, t.config, one, stream);
+}
+
+// Tunes the gather form and, for a 1x1 convolution, the batched-GEMM form; the faster one is remembered under
+// the convolution's key.
+hidet_status_t tune_conv(const ConvCall& cc, const SplitK& sk, hipStream_t stream, int iters, int32_t* best_config,
+                         int32_t* best_slices, float* best_us) {
+  int32_t c0 = -1, s0 = 1;
+  float t0 = 0.0f;
+  hidet_status_t st = tune(cc.conv, sk, stream, iters, &c0, &s0, &t0);
+  if (st != HIDET_OK) return st;
+  if (cc.pointwise) {
+    std::vector<float> times0;
+    {
+      std::lock_guard<std::mutex> lock(g_mutex);
+      times0 = g_last_times;
+    }
+    int32_t c1 = -1, s1 = 1;
+    float t1 = 0.0f;
+    st = tune(cc.gemm, sk, stream, iters, &c1, &s1, &t1);
+    if (st != HIDET_OK) return st;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (size_t i = 0; i < g_last_times.size() && i < times0.size(); ++i)
+      if (times0[i] >= 0.0f && (g_last_times[i] < 0.0f || times0[i] < g_last_times[i])) g_last_times[i] = times0[i];
+    if (c1 >= 0 && (c0 < 0 || t1 < t0)) {
+      g_cache[problem_key(cc.conv, sk.workspace != nullptr)] = Tuned{c1, s1, 1};
+      c0 = c1;
+      s0 = s1;
+      t0 = t1;
+    }
+  }
+  if (best_config) *best_config = c0;
+  if (best_slices) *best_slices = s0;
+  if (best_us) *best_us = t0;
+  return HIDET_OK;
 }
 
 // ---- task-mapping instances exposed to tests ----------------------------------------------------------
@@ -620,12 +701,12 @@ hidet_status_t hidet_conv2d_implicit_gemm_cfg(int32_t config, int32_t in, int32_
                                               int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                                               const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
                                               void* stream) {
-  Problem pr;
-  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
-                                        y, epi);
+  ConvCall cc;
+  hidet_status_t st = make_conv_call(cc, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                     epi);
   if (st != HIDET_OK) return st;
   if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
-  return guarded([&] { return launch(pr, config, SplitK{}, (hipStream_t)stream); });
+  return guarded([&] { return launch_conv(cc, config, SplitK{}, (hipStream_t)stream); });
 }
 
 hidet_status_t hidet_conv2d_implicit_gemm(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W,
@@ -675,11 +756,11 @@ hidet_status_t hidet_tune_conv2d(int32_t in, int32_t out, int64_t Nb, int64_t IC
                                  int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
                                  int64_t pad_w, const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
                                  void* stream, int32_t iters, int32_t* best_config, float* best_us) {
-  Problem pr;
-  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
-                                        y, epi);
+  ConvCall cc;
+  hidet_status_t st = make_conv_call(cc, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                     epi);
   if (st != HIDET_OK) return st;
-  return guarded([&] { return tune(pr, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us); });
+  return guarded([&] { return tune_conv(cc, SplitK{}, (hipStream_t)stream, iters, best_config, nullptr, best_us); });
 }
 
 // ---- K-parallel ("split-K") forms ------------------------------------------------------------------------------
@@ -712,9 +793,9 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
                                                  int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                                                  const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
                                                  void* workspace, int64_t workspace_bytes, void* stream) {
-  Problem pr;
-  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
-                                        y, epi);
+  ConvCall cc;
+  hidet_status_t st = make_conv_call(cc, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                     epi);
   if (st != HIDET_OK) return st;
   if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
   if (workspace_bytes < 0 || k_slices > 1024) return HIDET_ERR_INVALID_ARG;
@@ -722,7 +803,7 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
   sk.slices = k_slices <= 0 ? -1 : k_slices;
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
-  return guarded([&] { return launch(pr, config, sk, (hipStream_t)stream); });
+  return guarded([&] { return launch_conv(cc, config, sk, (hipStream_t)stream); });
 }
 
 hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
@@ -747,15 +828,15 @@ hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int
                                         const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes,
                                         void* stream, int32_t iters, int32_t* best_config, int32_t* best_slices,
                                         float* best_us) {
-  Problem pr;
-  hidet_status_t st = make_conv_problem(pr, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w,
-                                        y, epi);
+  ConvCall cc;
+  hidet_status_t st = make_conv_call(cc, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                     epi);
   if (st != HIDET_OK) return st;
   if (!workspace || workspace_bytes <= 0) return HIDET_ERR_INVALID_ARG;
   SplitK sk;
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
-  return guarded([&] { return tune(pr, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us); });
+  return guarded([&] { return tune_conv(cc, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us); });
 }
 
 int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity) {
@@ -776,7 +857,8 @@ hidet_status_t hidet_tune_save(const char* path) {
   std::lock_guard<std::mutex> lock(g_mutex);
   FILE* f = std::fopen(path, "w");
   if (!f) return HIDET_ERR_INVALID_ARG;
-  for (const auto& kv : g_cache) std::fprintf(f, "%s %d %d\n", kv.first.c_str(), kv.second.config, kv.second.slices);
+  for (const auto& kv : g_cache)
+    std::fprintf(f, "%s %d %d %d\n", kv.first.c_str(), kv.second.config, kv.second.slices, kv.second.route);
   std::fclose(f);
   return HIDET_OK;
 }
@@ -785,12 +867,15 @@ hidet_status_t hidet_tune_load(const char* path) {
   if (!path) return HIDET_ERR_INVALID_ARG;
   FILE* f = std::fopen(path, "r");
   if (!f) return HIDET_ERR_INVALID_ARG;
-  char key[256];
-  int cfg = 0, slices = 1;
+  char line[512], key[256];
   const hidet_status_t st = guarded([&] {
     std::lock_guard<std::mutex> lock(g_mutex);
-    while (std::fscanf(f, "%255s %d %d", key, &cfg, &slices) == 3)
-      if (cfg >= 0 && cfg < kNumConfigs && slices >= 1 && slices <= 1024) g_cache[std::string(key)] = Tuned{cfg, slices};
+    while (std::fgets(line, sizeof(line), f)) {
+      int cfg = 0, slices = 1, route = 0;  // the route is absent from files written before it existed
+      if (std::sscanf(line, "%255s %d %d %d", key, &cfg, &slices, &route) < 3) continue;
+      if (cfg >= 0 && cfg < kNumConfigs && slices >= 1 && slices <= 1024 && (route == 0 || route == 1))
+        g_cache[std::string(key)] = Tuned{cfg, slices, route};
+    }
     return HIDET_OK;
   });
   std::fclose(f);

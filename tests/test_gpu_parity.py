@@ -231,6 +231,49 @@ def test_conv_gather_windows(dtype):
         assert within_bound(err, ref, dtype), (i, err)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_pointwise_convolutions_in_both_forms(dtype):
+    """A 1x1, stride-1, unpadded convolution runs as a batched GEMM (weights shared over the batch) when no
+    configuration is named and through the gather when one is: both against the oracle, unsliced and K-sliced,
+    image sizes that allow 16-byte rows and sizes that do not, then once more after tuning has chosen between them."""
+    cases = [(2, 64, 16, 24, 96), (3, 40, 7, 7, 72), (1, 33, 14, 14, 50), (4, 128, 28, 28, 64), (2, 17, 5, 9, 3),
+             (1, 8, 1, 1, 5), (5, 1, 3, 3, 1)]
+    hb.hidet_tune_clear()
+    for i, (Nb, IC, H, W, OC) in enumerate(cases):
+        c = wl.conv_case(7750 + i, Nb, IC, H, W, OC, 1, 1, 1, 0, dtype, residual=bool(i % 2))
+        c.update(relu=bool((i + 1) % 3), alpha=[1.0, 0.5][i % 2])
+        _say("pointwise %s case %d: %dx%dx%dx%d -> %d" % (dtype, i, Nb, IC, H, W, OC))
+        err_g, got_g, ref = run_conv_case(c)  # batched-GEMM form
+        assert within_bound(err_g, ref, dtype), (i, err_g)
+        err_c, got_c, _ = run_conv_case(c, config=applicable_configs(dtype)[i % 5])  # gather form
+        assert within_bound(err_c, ref, dtype), (i, err_c)
+        assert oracle.rel_frobenius(got_g, got_c) <= 2 * TOL[dtype] + 1e-5 or ref.size < 64
+        err, _, _ = run_conv_case(c, k_slices=3)
+        assert within_bound(err, ref, dtype), (i, err)
+        err, _, _ = run_conv_case(c, k_slices=2, config=sliceable_configs(dtype)[i % 3])
+        assert within_bound(err, ref, dtype), (i, err)
+    # the tuner enumerates both forms and the remembered choice is what an unnamed configuration then runs
+    c = wl.conv_case(7760, 4, 128, 28, 28, 64, 1, 1, 1, 0, dtype)
+    c.update(relu=True)
+    x, w, bias = to_gpu(c["x"], dtype), to_gpu(c["w"], dtype), to_gpu(c["bias"], dtype)
+    y = torch.empty((4, 64, 28, 28), dtype=TORCH_DTYPE[dtype], device="cuda")
+    epi = hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+    cfg, us = hb.hidet_tune_conv2d(x, w, y, epilogue=epi, iters=3)
+    times = [t for t in hb.hidet_tune_last_times() if t > 0]
+    assert cfg in applicable_configs(dtype) and us > 0 and abs(us - min(times)) <= 1e-3 * us
+    err, _, ref = run_conv_case(c)
+    assert within_bound(err, ref, dtype), err
+    ws = make_workspace(1, 64, hb.conv_gemm_n(y.shape), 16)
+    cfg, slices, us = hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=3)
+    assert slices >= 1 and us > 0
+    y.fill_(float("nan"))
+    hb.hidet_conv2d_implicit_gemm_splitk(x, w, y, ws, k_slices=0, epilogue=epi)  # the remembered (form, tile, slices)
+    torch.cuda.synchronize()
+    err = oracle.rel_frobenius(to_f64(y), ref)
+    assert within_bound(err, ref, dtype), err
+    hb.hidet_tune_clear()
+
+
 # ------------------------------------------------------------------ output index map (reshape-matmul-transpose)
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_head_split_output_map(dtype):
@@ -390,7 +433,7 @@ def test_tuner_enumerates_the_space_and_caches(tmp_path):
     path = str(tmp_path / "tuned.txt")
     hb.hidet_tune_save(path)
     text = open(path).read()
-    assert "gemm:t1:00:b1:128x768x256" in text and text.strip().endswith("%d 1" % best)
+    assert "gemm:t1:00:b1:128x768x256" in text and text.strip().endswith("%d 1 0" % best)
     hb.hidet_tune_clear()
     hb.hidet_tune_load(path)
     C.zero_()

@@ -209,6 +209,22 @@ def test_splitk_argument_validation():
                                     None, 0, None, 3, ctypes.byref(i), ctypes.byref(i), ctypes.byref(f)) == 1
 
 
+def test_tuned_cache_file_round_trip(tmp_path):
+    """The cache is a text file of `key configuration slices form` lines; lines without the last field (files written
+    before it existed) load with form 0, malformed or out-of-range lines are skipped."""
+    L = hb.lib()
+    src, dst = tmp_path / "in.txt", tmp_path / "out.txt"
+    src.write_text("gemm:t1:00:b1:8x8x8:e0:m0 3 2\nconv:t1:n1:c4:8x8:o4:k1x1:s1x1:p0x0:e0:m0 5 1 1\nnot a line\n"
+                   "gemm:t1:00:b1:9x9x9:e0:m0 100000 1 0\ngemm:t1:00:b1:7x7x7:e0:m0 2 1 7\n")
+    L.hidet_tune_clear()
+    assert L.hidet_tune_load(str(src).encode()) == 0
+    assert L.hidet_tune_save(str(dst).encode()) == 0
+    L.hidet_tune_clear()
+    lines = sorted(dst.read_text().split("\n"))
+    assert lines == ["", "conv:t1:n1:c4:8x8:o4:k1x1:s1x1:p0x0:e0:m0 5 1 1", "gemm:t1:00:b1:8x8x8:e0:m0 3 2 0"]
+    assert L.hidet_tune_load(str(tmp_path / "missing.txt").encode()) == 1 and L.hidet_tune_load(None) == 1
+
+
 def test_multiply_shift_division_equals_floor_division():
     """The divider the kernels use for index arithmetic, checked where such schemes go wrong: every n for small
     divisors, and the neighbourhood of every multiple near the top of the 31-bit range for a spread of divisors."""
