@@ -310,8 +310,8 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
   return registry().fn[config][pr.dtype][kPartialVariants + variant];
 }
 
-// Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the tile
-// with the most workgroups.  Outputs large enough to be bound by throughput rather than by one workgroup's
+// Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the largest
+// that gives a quarter of them one, else the tile with the most workgroups.  Outputs large enough to be bound by throughput rather than by one workgroup's
 // latency chain (at least 384 tiles of 64x64) ask for about two workgroups per compute unit instead, so that one
 // workgroup's loads and output write overlap another's arithmetic -- except from the ring schedule on a long K,
 // which overlaps them inside the workgroup.  Between tiles of one size the ring schedule, the 16x16 matrix-core
@@ -325,8 +325,8 @@ int default_config(const Problem& pr, int slices = 1) {
     return (long long)r.bm * r.bn * 8 + (r.sched == 1 ? 4 : 0) + (r.mfma == 16 ? 2 : 0) + ahead;
   };
   const bool throughput = sat_mul(((M + 63) / 64) * ((N + 63) / 64), pr.batch) >= 384;
-  int best = -1, most = -1;
-  long long most_blocks = -1, best_key = -(1LL << 62);
+  int best = -1, fewer = -1, most = -1;
+  long long most_blocks = -1, best_key = -(1LL << 62), fewer_key = -(1LL << 62);
   for (int c = 0; c < kNumConfigs; ++c) {
     if (!find_launcher(pr, c)) continue;
     if (slices > 1 && !find_partial_launcher(pr, c)) continue;
@@ -351,12 +351,25 @@ int default_config(const Problem& pr, int slices = 1) {
       best = c;
       best_key = key;
     }
-    if (blocks > most_blocks || (blocks == most_blocks && rank(r) > rank(kConfigs[most]))) {
+    // second choice when no tile gives that many workgroups: the same order among the tiles that still give 64
+    if (blocks >= 64 && key > fewer_key) {
+      fewer = c;
+      fewer_key = key;
+    }
+    // last resort (not even 64 workgroups): the most workgroups; between equals the smaller tile, then the deeper K
+    // tile that K still fills (one workgroup's latency chain is all there is to shorten), then the preferences
+    auto beats = [&](const ConfigRow& a, const ConfigRow& b) {
+      if (a.bm * a.bn != b.bm * b.bn) return a.bm * a.bn < b.bm * b.bn;
+      const int ka = a.bk <= pr.p.K ? a.bk : 0, kb = b.bk <= pr.p.K ? b.bk : 0;
+      if (ka != kb) return ka > kb;
+      return rank(a) > rank(b);
+    };
+    if (blocks > most_blocks || (blocks == most_blocks && beats(r, kConfigs[most]))) {
       most_blocks = blocks;
       most = c;
     }
   }
-  return best >= 0 ? best : most;
+  return best >= 0 ? best : (fewer >= 0 ? fewer : most);
 }
 
 // ---- tuned-config cache ---------------------------------------------------------------------------
