@@ -253,7 +253,9 @@ hidet_status_t hidet_tune_conv2d_splitk(int32_t in, int32_t out, int64_t Nb, int
 int32_t hidet_tune_last_times(float* us_per_config, int32_t capacity);
 /* Forget every tuned entry. */
 void hidet_tune_clear(void);
-/* Persist / restore the tuned-config cache as a text file (host paths).  Returns HIDET_ERR_INVALID_ARG on I/O errors. */
+/* Persist / restore the tuned-config cache as a text file (host paths): one line `key config k_slices form` per
+ * problem (form: 1 = batched-GEMM form of a 1x1 convolution, else 0; a line without it reads as 0; malformed or
+ * out-of-range lines are skipped).  Returns HIDET_ERR_INVALID_ARG on I/O errors. */
 hidet_status_t hidet_tune_save(const char* path);
 hidet_status_t hidet_tune_load(const char* path);
 
