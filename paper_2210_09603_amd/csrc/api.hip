@@ -311,18 +311,21 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
 }
 
 // Untuned choice: the largest tile that still gives (nearly) every compute unit a workgroup, else the largest
-// that gives a quarter of them one, else the tile with the most workgroups.  Outputs large enough to be bound by throughput rather than by one workgroup's
-// latency chain (at least 384 tiles of 64x64) ask for about two workgroups per compute unit instead, so that one
-// workgroup's loads and output write overlap another's arithmetic -- except from the ring schedule on a long K,
-// which overlaps them inside the workgroup.  Between tiles of one size the ring schedule, the 16x16 matrix-core
-// shape and (small tiles) the loads-ahead order are preferred (they measure faster wherever both apply); the
-// tiles that split K over wave groups take part only when K spans at least one of their K tiles and the output
-// is small.  With slices > 1 only tiles that have a K-parallel form take part.
+// that gives a quarter of them one, else the tile with the most workgroups.  Outputs large enough to be bound by
+// throughput rather than by one workgroup's latency chain (at least 384 tiles of 64x64) ask for about two
+// workgroups per compute unit instead, so that one workgroup's loads and output write overlap another's
+// arithmetic -- except from the ring schedule on four or more stages of K, which overlaps them inside the
+// workgroup and needs just over half a round of workgroups.  Between tiles of one size the ring schedule, the
+// 16x16 matrix-core shape and (small tiles) the loads-ahead order are preferred (they measure faster wherever
+// both apply); the tiles that split K over wave groups take part only when K spans at least one of their K tiles
+// and the output is small.  With slices > 1 only tiles that have a K-parallel form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
-  auto rank = [](const ConfigRow& r) {
+  const bool long_k = pr.p.K >= 2048;
+  auto rank = [long_k](const ConfigRow& r) {
     const int ahead = (r.sched == 2 && r.bm * r.bn <= 64 * 64) ? 1 : 0;  // measured faster on small tiles only
-    return (long long)r.bm * r.bn * 8 + (r.sched == 1 ? 4 : 0) + (r.mfma == 16 ? 2 : 0) + ahead;
+    const int ksplit = (r.sched == 3 && long_k) ? 2 : 0;  // where they take part at all, they win on a long K
+    return (long long)r.bm * r.bn * 8 + (r.sched == 1 ? 4 : 0) + (r.mfma == 16 ? 2 : 0) + ahead + ksplit;
   };
   const bool throughput = sat_mul(((M + 63) / 64) * ((N + 63) / 64), pr.batch) >= 384;
   int best = -1, fewer = -1, most = -1;
@@ -335,13 +338,19 @@ int default_config(const Problem& pr, int slices = 1) {
     if (r.sched == 3 && (pr.p.K < r.bk || throughput)) continue;
     const long long blocks =
         sat_mul(((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn), pr.batch * (slices > 1 ? slices : 1));
-    // (the ring schedule proper runs GEMMs with 16-byte aligned operands only)
-    const bool ring = r.sched == 1 && pr.op == 0 && pr.elem_mode == 0 && pr.p.out_map == 0;
-    const long long enough = (throughput && !(ring && pr.p.K > 128)) ? 400 : 192;
+    // the ring schedule runs GEMMs only: by direct-to-LDS loads when the operands are 16-byte aligned, with its
+    // stages staged through registers when they are not
+    const bool ring_any = r.sched == 1 && pr.op == 0 && pr.p.out_map == 0;
+    const bool ring = ring_any && pr.elem_mode == 0;
+    // A ring tile keeps one workgroup per compute unit busy on its own (from four stages of K on).  With 129..191
+    // of them the tile of half the size would need a second, mostly empty round of workgroups, so the larger one is
+    // still the better choice; from 128 down the smaller tile fits into one round and wins.
+    const long long area = (long long)r.bm * r.bn;
+    const bool self_overlapping = ring_any && pr.p.K >= 128;
+    const long long enough = !throughput ? 192 : !self_overlapping ? 400 : 129;
 
     // useful outputs per workgroup, discounted by the share of the tile that is padding, decide; then the smaller
     // tile, then the schedule preferences
-    const long long area = (long long)r.bm * r.bn;
     const long long useful = (M * N) / (((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn));
     long long key = (useful * useful / area) * (1LL << 23) - area * 64 + (rank(r) & 63);
     // a K of at most two stages runs the two-slot ring: two workgroups of a 256x128 tile share a compute unit and
