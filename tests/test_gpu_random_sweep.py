@@ -74,6 +74,26 @@ def test_random_convs(seed):
         assert within_bound(err, ref, dtype), what + " err %.3e" % err
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_random_pointwise_convs(seed):
+    """1x1, stride-1, unpadded convolutions with no configuration named: the batched-GEMM form, unsliced and K-sliced,
+    over image sizes with and without 16-byte aligned rows."""
+    g = np.random.default_rng(9700 + seed)
+    for case in range(10):
+        dtype = DTYPES[int(g.integers(3))]
+        Nb, IC, OC = int(g.integers(1, 6)), _log_uniform(g, 1, 300), _log_uniform(g, 1, 200)
+        H, W = _log_uniform(g, 1, 30), _log_uniform(g, 1, 30)
+        k_slices = int(g.integers(2, 6)) if g.integers(3) == 0 else None
+        c = wl.conv_case(9700 + 100 * seed + case, Nb, IC, H, W, OC, 1, 1, 1, 0, dtype,
+                         bias=bool(g.integers(2)), residual=bool(g.integers(2)))
+        c["relu"] = bool(g.integers(2))
+        c["alpha"] = [1.0, 0.5, -1.5][int(g.integers(3))]
+        what = "seed %d case %d: %s N%d %d->%d %dx%d slices %s" % (seed, case, dtype, Nb, IC, OC, H, W, k_slices)
+        print(what, flush=True)
+        err, _, ref = run_conv_case(c, k_slices=k_slices)
+        assert within_bound(err, ref, dtype), what + " err %.3e" % err
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_batched_wide_and_head_split(seed):
     """The remaining forms of the GEMM interface, drawn at random: batches with an operand shared by all entries
