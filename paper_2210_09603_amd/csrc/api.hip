@@ -321,7 +321,9 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
 // and the output is small.  With slices > 1 only tiles that have a K-parallel form take part.
 int default_config(const Problem& pr, int slices = 1) {
   const long long M = pr.p.M, N = pr.p.N;
-  const bool long_k = pr.p.K >= 2048;
+  // (measured: equal to the two-stage tiles of their size at K = 1024, ahead beyond; the gather of the convolution
+  // moves that point to about 512)
+  const bool long_k = pr.p.K >= (pr.op == 1 ? 512 : 1024);
   auto rank = [long_k](const ConfigRow& r) {
     const int ahead = (r.sched == 2 && r.bm * r.bn <= 64 * 64) ? 1 : 0;  // measured faster on small tiles only
     const int ksplit = (r.sched == 3 && long_k) ? 2 : 0;  // where they take part at all, they win on a long K
