@@ -147,6 +147,27 @@ def test_rows_subset_and_batched():
     assert np.array_equal(oracle.batched_gemm(Ab, Bt, transB=True), oracle.batched_gemm(Ab, Bb))
 
 
+def test_batched_bias_is_shared_and_residual_advances_per_entry():
+    """The bias of a batched product is one vector shared by every entry (per column or per row); only the
+    residual advances with the batch index.  Each entry must equal the plain product of that entry."""
+    g = np.random.default_rng(16)
+    Ab, Bb = g.standard_normal((5, 4, 7)), g.standard_normal((5, 7, 6))
+    res = g.standard_normal((5, 4, 6))
+    for axis, n in ((BIAS_PER_COL, 6), (BIAS_PER_ROW, 4)):
+        bias = g.standard_normal(n)
+        Cb = oracle.batched_gemm(Ab, Bb, alpha=-0.75, bias=bias, bias_axis=axis, residual=res, relu=True)
+        for b in range(5):
+            one = oracle.gemm(Ab[b], Bb[b], alpha=-0.75, bias=bias, bias_axis=axis, residual=res[b], relu=True)
+            assert np.array_equal(Cb[b], one), (axis, b)
+    # closed form: all-ones entries of length K with a per-column bias give K + bias[j] in every entry
+    bias = np.arange(6, dtype=np.float64) - 2.0
+    Cb = oracle.batched_gemm(np.ones((3, 4, 7)), np.ones((3, 7, 6)), bias=bias, bias_axis=BIAS_PER_COL)
+    assert np.array_equal(Cb, np.broadcast_to(7.0 + bias, (3, 4, 6)))
+    rb = np.array([0.5, -1.0, 2.0, 8.0])
+    Cb = oracle.batched_gemm(np.ones((3, 4, 7)), np.ones((3, 7, 6)), bias=rb, bias_axis=BIAS_PER_ROW)
+    assert np.array_equal(Cb, np.broadcast_to(7.0 + rb[:, None], (3, 4, 6)))
+
+
 def test_degenerate_shapes():
     assert oracle.gemm(np.zeros((0, 4)), np.zeros((4, 3))).shape == (0, 3)
     assert oracle.gemm(np.zeros((2, 4)), np.zeros((4, 0))).shape == (2, 0)
@@ -214,6 +235,64 @@ def test_conv_residual_and_relu_order():
     res = np.array([[[[0.5, 1.5], [2.0, 0.0]]]])
     y = oracle.conv2d(x, w, bias=np.array([0.25]), residual=res, relu=True)
     assert np.array_equal(y, np.array([[[[0.0, 0.75], [1.25, 0.0]]]]))
+
+
+def _exact_conv(x, w, stride, pad, alpha, bias, residual, relu):
+    """Direct convolution in exact rationals (integer-valued inputs), loops in another order than the oracle's."""
+    Nb, IC, H, W = x.shape
+    OC, _, KH, KW = w.shape
+    OH = (H + 2 * pad[0] - KH) // stride[0] + 1
+    OW = (W + 2 * pad[1] - KW) // stride[1] + 1
+    out = np.empty((Nb, OC, OH, OW), dtype=object)
+    for ow in range(OW):
+        for oh in range(OH):
+            for oc in range(OC):
+                for n in range(Nb):
+                    s = Fraction(0)
+                    for kw in range(KW):
+                        for kh in range(KH):
+                            ih, iw = oh * stride[0] + kh - pad[0], ow * stride[1] + kw - pad[1]
+                            if 0 <= ih < H and 0 <= iw < W:
+                                for ic in range(IC):
+                                    s += Fraction(int(x[n, ic, ih, iw])) * Fraction(int(w[oc, ic, kh, kw]))
+                    v = Fraction(alpha) * s
+                    if bias is not None:
+                        v += Fraction(int(bias[oc]))
+                    if residual is not None:
+                        v += Fraction(int(residual[n, oc, oh, ow]))
+                    if relu and v < 0:
+                        v = Fraction(0)
+                    out[n, oc, oh, ow] = v
+    return out
+
+
+@pytest.mark.parametrize("alpha", [0.25, -1.5, 0.0])
+@pytest.mark.parametrize("flags", range(8))
+def test_conv_alpha_scales_the_sum_before_bias_residual_and_relu(alpha, flags):
+    """The scale of the fused epilogue multiplies the convolution sum only: exact rationals on integer data,
+    for every combination of bias / residual / ReLU."""
+    g = np.random.default_rng(17 + flags)
+    x = g.integers(-4, 5, size=(2, 3, 5, 6)).astype(np.float64)
+    w = g.integers(-3, 4, size=(4, 3, 3, 2)).astype(np.float64)
+    stride, pad = (2, 1), (1, 1)
+    bias = g.integers(-9, 10, size=4).astype(np.float64) if flags & 1 else None
+    y0 = oracle.conv2d(x, w, stride=stride, pad=pad)
+    res = g.integers(-9, 10, size=y0.shape).astype(np.float64) if flags & 2 else None
+    relu = bool(flags & 4)
+    y = oracle.conv2d(x, w, stride=stride, pad=pad, alpha=alpha, bias=bias, residual=res, relu=relu)
+    exact = _exact_conv(x, w, stride, pad, alpha, bias, res, relu)
+    assert y.shape == exact.shape
+    for got, want in zip(y.ravel(), exact.ravel()):
+        assert Fraction(float(got)) == want
+    # and against alpha * (the unscaled convolution): alpha is a dyadic rational, so the product is exact
+    v = alpha * y0
+    if bias is not None:
+        v = v + bias[None, :, None, None]
+    if res is not None:
+        v = v + res
+    if relu:
+        v = np.maximum(v, 0.0)
+    assert np.array_equal(y, v)
 
 
 # ---------------------------------------------------------------- the error measure itself
