@@ -25,6 +25,61 @@ def within_bound(err, ref, dtype):
     return err <= max(TOL[dtype], 1.1 * output_rounding_floor(ref, dtype) + 1e-5)
 
 
+# Per-element parity bound.  A relative Frobenius norm over millions of outputs hides a single wrong element, so
+# every comparison also bounds each element on its own:
+#     |got - ref| <= REL * |ref| + ACC * scale + FLOOR
+#   REL    twice the half-ulp of the one RNE rounding to the output type (2^-11 fp16, 2^-8 bf16, 2^-24 fp32);
+#   scale  |alpha| * ||A_i||_2 * ||B_j||_2 + |bias| + |residual|: what the fp32 accumulation error is proportional
+#          to (Cauchy-Schwarz bound on sum |a_k b_k|);  ACC = 1e-5 for K up to 4096 and grows with sqrt(K) beyond --
+#          a random-walk fp32 sum of K terms errs by about sqrt(K) * 2^-24 of the term magnitude, far below that;
+#   FLOOR  the spacing of fp16 subnormals (outputs below 6.1e-5 are rounded on an absolute grid).
+ELEM_REL = {"f32": 2.0 ** -22, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}
+ELEM_FLOOR = {"f32": 1e-30, "f16": 2.0 ** -24, "bf16": 1e-30}
+
+
+def acc_coeff(K):
+    return 1e-5 * max(1.0, (K / 4096.0) ** 0.5)
+
+
+def elementwise_violations(got, ref, scale, dtype, K):
+    """Number of elements outside the per-element bound, and the worst ratio error / bound."""
+    bound = ELEM_REL[dtype] * np.abs(ref) + acc_coeff(K) * scale + ELEM_FLOOR[dtype]
+    ratio = np.abs(got - ref) / bound
+    return int(np.count_nonzero(~(ratio <= 1.0))), float(np.nanmax(ratio)) if ratio.size else 0.0
+
+
+def assert_elementwise(got, ref, scale, dtype, K, what=""):
+    bad, worst = elementwise_violations(got, ref, scale, dtype, K)
+    assert bad == 0, "%s: %d of %d elements outside the per-element bound (worst %.2f x bound)" % (what, bad, ref.size, worst)
+    return worst
+
+
+def gemm_scale(A64, B64, transA, transB, alpha, bias=None, bias_axis=None, residual=None):
+    """|alpha| * ||row i of op(A)|| * ||column j of op(B)|| + |bias| + |residual| for every output element."""
+    na = np.sqrt((A64 * A64).sum(axis=0 if transA else 1))
+    nb = np.sqrt((B64 * B64).sum(axis=1 if transB else 0))
+    s = abs(alpha) * np.outer(na, nb)
+    if bias is not None:
+        s = s + (np.abs(bias)[:, None] if bias_axis == "row" else np.abs(bias)[None, :])
+    if residual is not None:
+        s = s + np.abs(residual)
+    return s
+
+
+def conv_scale(x64, w64, stride, pad, alpha, bias=None, residual=None):
+    """The same for a convolution: ||w[oc]|| * ||receptive field of the output position|| (the latter from the
+    convolution of x^2 with an all-ones filter)."""
+    OC = w64.shape[0]
+    field = oracle.conv2d(x64 * x64, np.ones((1,) + w64.shape[1:]), stride=stride, pad=pad)  # [Nb,1,OH,OW]
+    nw = np.sqrt((w64 * w64).reshape(OC, -1).sum(axis=1))
+    s = abs(alpha) * nw[None, :, None, None] * np.sqrt(np.maximum(field, 0.0))
+    if bias is not None:
+        s = s + np.abs(bias)[None, :, None, None]
+    if residual is not None:
+        s = s + np.abs(residual)
+    return s
+
+
 def to_gpu(stored, dtype):
     """Stored host array (workloads representation) -> GPU tensor with the same bits."""
     if stored is None:
@@ -52,6 +107,12 @@ def oracle_bias_axis(axis):
 def make_workspace(batch, M, N, k_slices):
     """fp32 workspace of the K-parallel entry points, filled with NaN so that a stale read shows."""
     n = hb.hidet_splitk_workspace_bytes(batch, M, N, max(k_slices, 1)) // 4
+    return torch.full((max(n, 4),), float("nan"), dtype=torch.float32, device="cuda")
+
+
+def make_conv_workspace(y_shape, k_slices):
+    """The same for the K-parallel convolution that writes y [Nb, OC, OH, OW]."""
+    n = hb.hidet_conv2d_splitk_workspace_bytes(tuple(y_shape), max(k_slices, 1)) // 4
     return torch.full((max(n, 4),), float("nan"), dtype=torch.float32, device="cuda")
 
 
@@ -83,6 +144,10 @@ def run_gemm_case(c, config=-1, relu=None, alpha=None, k_slices=None):
                       bias_axis=oracle_bias_axis(c["bias_axis"]),
                       residual=None if c["residual"] is None else wl.widen(c["residual"], dt), relu=relu)
     got = to_f64(C)
+    assert_elementwise(got, ref, gemm_scale(A64, B64, c["transA"], c["transB"], alpha,
+                                            None if c["bias"] is None else wl.widen(c["bias"], dt), c["bias_axis"],
+                                            None if c["residual"] is None else wl.widen(c["residual"], dt)),
+                       dt, K, "gemm %dx%dx%d %s config %d" % (M, N, K, dt, config))
     return oracle.rel_frobenius(got, ref), got, ref
 
 
@@ -99,7 +164,7 @@ def run_conv_case(c, config=-1, k_slices=None):
     if k_slices is None:
         hb.hidet_conv2d_implicit_gemm(x, w, y, stride=stride, pad=pad, epilogue=epi, config=config)
     else:
-        ws = make_workspace(1, y.shape[1], hb.conv_gemm_n(y.shape), k_slices)
+        ws = make_conv_workspace(y.shape, k_slices)
         hb.hidet_conv2d_implicit_gemm_splitk(x, w, y, ws, k_slices=k_slices, stride=stride, pad=pad, epilogue=epi,
                                              config=config)
     torch.cuda.synchronize()
@@ -107,6 +172,11 @@ def run_conv_case(c, config=-1, k_slices=None):
                         bias=None if c["bias"] is None else wl.widen(c["bias"], dt),
                         residual=None if c["residual"] is None else wl.widen(c["residual"], dt), relu=c.get("relu", False))
     got = to_f64(y)
+    x64, w64 = wl.widen(c["x"], dt), wl.widen(c["w"], dt)
+    assert_elementwise(got, ref, conv_scale(x64, w64, stride, pad, c.get("alpha", 1.0),
+                                            None if c["bias"] is None else wl.widen(c["bias"], dt),
+                                            None if c["residual"] is None else wl.widen(c["residual"], dt)),
+                       dt, w64[0].size, "conv %s config %d" % (c.get("name", tuple(x.shape)), config))
     return oracle.rel_frobenius(got, ref), got, ref
 
 

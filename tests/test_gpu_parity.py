@@ -7,7 +7,7 @@ import oracle
 from paper_2210_09603_amd import binding as hb
 from paper_2210_09603_amd import workloads as wl
 
-from helpers import (TOL, TORCH_DTYPE, applicable_configs, make_workspace, run_conv_case, run_gemm_case, sliceable_configs,
+from helpers import (TOL, TORCH_DTYPE, applicable_configs, assert_elementwise, make_conv_workspace, make_workspace, run_conv_case, run_gemm_case, sliceable_configs,
                      to_f64, to_gpu, within_bound)
 
 pytestmark = pytest.mark.gpu
@@ -41,22 +41,31 @@ def test_config3_resnet50_convs(dtype):
         assert err <= TOL[dtype]
 
 
-@pytest.mark.parametrize("batch,seq", [(12, 128), (12, 512), (192, 128)])
-def test_config4_attention_products(batch, seq):
-    c = wl.attention_case(4000 + batch + seq, batch, seq, "f16")
+@pytest.mark.parametrize("case", range(4))
+def test_config4_attention_products(case):
+    """All four cases of the benchmark configuration (batch x heads in {12, 192}, seq in {128, 512}), the very
+    tensors bench.py's side report times (workloads.config4: seeds 4000 + case), untuned launch configuration;
+    every batch entry as a tensor of its own, the whole batch as one, and every element on its own."""
+    c = wl.config4("f16")[case]
+    batch, seq = c["batch"], c["seq"]
     Q, K, V, S = (to_gpu(c[k], "f16") for k in ("Q", "K", "V", "S"))
     scores = torch.full((batch, seq, seq), float("nan"), dtype=torch.float16, device="cuda")
     hb.hidet_batched_gemm(Q, K, scores, transB=True, epilogue=hb.make_epilogue(alpha=c["alpha"]))
     ctx = torch.full((batch, seq, c["d"]), float("nan"), dtype=torch.float16, device="cuda")
     hb.hidet_batched_gemm(S, V, ctx)
     torch.cuda.synchronize()
-    ref_s = oracle.batched_gemm(wl.widen(c["Q"], "f16"), wl.widen(c["K"], "f16"), transB=True, alpha=c["alpha"])
-    ref_c = oracle.batched_gemm(wl.widen(c["S"], "f16"), wl.widen(c["V"], "f16"))
+    Q64, K64, S64, V64 = (wl.widen(c[k], "f16") for k in ("Q", "K", "S", "V"))
+    ref_s = oracle.batched_gemm(Q64, K64, transB=True, alpha=c["alpha"])
+    ref_c = oracle.batched_gemm(S64, V64)
     got_s, got_c = to_f64(scores), to_f64(ctx)
     worst = max(max(oracle.rel_frobenius(got_s[b], ref_s[b]) for b in range(batch)), oracle.rel_frobenius(got_s, ref_s),
                 max(oracle.rel_frobenius(got_c[b], ref_c[b]) for b in range(batch)), oracle.rel_frobenius(got_c, ref_c))
     _say("cfg4 b%d s%d worst err %.3e" % (batch, seq, worst))
     assert worst <= TOL["f16"]
+    nq, nk = np.sqrt((Q64 * Q64).sum(-1)), np.sqrt((K64 * K64).sum(-1))
+    assert_elementwise(got_s, ref_s, c["alpha"] * nq[:, :, None] * nk[:, None, :], "f16", c["d"], "cfg4 scores")
+    ns, nv = np.sqrt((S64 * S64).sum(-1)), np.sqrt((V64 * V64).sum(-2))
+    assert_elementwise(got_c, ref_c, ns[:, :, None] * nv[:, None, :], "f16", seq, "cfg4 context")
 
 
 # ------------------------------------------------------------------ sizes that are not multiples of anything
@@ -263,7 +272,7 @@ def test_pointwise_convolutions_in_both_forms(dtype):
     assert cfg in applicable_configs(dtype) and us > 0 and abs(us - min(times)) <= 1e-3 * us
     err, _, ref = run_conv_case(c)
     assert within_bound(err, ref, dtype), err
-    ws = make_workspace(1, 64, hb.conv_gemm_n(y.shape), 16)
+    ws = make_conv_workspace(y.shape, 16)
     cfg, slices, us = hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=3)
     assert slices >= 1 and us > 0
     y.fill_(float("nan"))
