@@ -234,6 +234,13 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
                                                  const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
                                                  void* workspace, int64_t workspace_bytes, void* stream);
 /*
+ * Workspace of the K-parallel convolution (Sections 5.2 and 6.3.4: the convolution is the matrix multiplication
+ * with GEMM M = OC and GEMM N = Nb*OH*roundup(OW, 8), the padded-row column order of the img2col prologue):
+ * bytes that hidet_conv2d_implicit_gemm_splitk needs for an output y[Nb][OC][OH][OW] cut into k_slices.
+ * Returns -1 under the conditions of hidet_splitk_workspace_bytes.
+ */
+int64_t hidet_conv2d_splitk_workspace_bytes(int64_t Nb, int64_t OC, int64_t OH, int64_t OW, int32_t k_slices);
+/*
  * Tuning over (configuration x k_slices in {1,2,3,4,6,8,12,16}) with the given workspace; slice
  * counts the workspace cannot hold are skipped.  Otherwise as hidet_tune_gemm / hidet_tune_conv2d;
  * the winner is remembered for the *_splitk entry points (k_slices <= 0, config < 0).

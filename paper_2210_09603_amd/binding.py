@@ -59,7 +59,7 @@ EXPORTS = (
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_probe_launch_floor", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
-    "hidet_softmax_rows", "hidet_host_div",
+    "hidet_softmax_rows", "hidet_host_div", "hidet_conv2d_splitk_workspace_bytes",
 )
 
 _lib = None
@@ -88,6 +88,8 @@ def lib():
         L.hidet_tune_conv2d.argtypes = conv_args + tune_tail
         L.hidet_splitk_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
         L.hidet_splitk_workspace_bytes.restype = _i64
+        L.hidet_conv2d_splitk_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _i32]
+        L.hidet_conv2d_splitk_workspace_bytes.restype = _i64
         ws_args = [_vp, _i64, _vp]  # workspace, bytes, stream (replaces the trailing stream argument)
         L.hidet_batched_gemm_splitk.argtypes = [_i32, _i32] + bgemm_args[:-1] + ws_args
         L.hidet_conv2d_implicit_gemm_splitk.argtypes = [_i32, _i32] + conv_args[:-1] + ws_args
@@ -147,12 +149,16 @@ def _ld(t):
 def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None, relu=False, batched=False,
                   head_split=None):
     """Build a hidet_epilogue_t (returns None for the identity epilogue).  head_split=(seq, head_dim) selects the
-    [b][h][s][f] output index map; the residual (if any) is then a dense tensor of that shape."""
+    [b][h][s][f] output index map; the residual (if any) is then a dense tensor of that shape.  A 3-D residual
+    advances by its own batch stride (`batched` is accepted for older callers and ignored)."""
     if alpha == 1.0 and bias is None and residual is None and not relu and head_split is None:
         return None
     e = hidet_epilogue_t()
     e.struct_size = ctypes.sizeof(hidet_epilogue_t)
     e.alpha = alpha
+    # the struct holds raw device addresses: keep the tensors alive as long as it lives (an asynchronous kernel
+    # reads them after the call has returned)
+    e._keep = (bias, residual)
     e.bias = bias.data_ptr() if bias is not None else None
     e.bias_axis = bias_axis if bias is not None else HIDET_BIAS_NONE
     e.act = HIDET_ACT_RELU if relu else HIDET_ACT_NONE
@@ -163,7 +169,7 @@ def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None
         e.residual = residual.data_ptr()
         if head_split is None:
             e.ld_residual = _ld(residual)
-            e.batch_stride_residual = residual.stride(0) if (batched and residual.dim() == 3) else 0
+            e.batch_stride_residual = residual.stride(0) if (residual.dim() == 3 and residual.shape[0] > 1) else 0
     return e
 
 
@@ -265,10 +271,10 @@ def hidet_splitk_workspace_bytes(batch, M, N, k_slices):
     return lib().hidet_splitk_workspace_bytes(batch, M, N, k_slices)
 
 
-def conv_gemm_n(y_shape):
-    """GEMM N of the implicit-GEMM convolution that produces y [Nb, OC, OH, OW]: output rows padded to 8 columns."""
-    Nb, _, OH, OW = y_shape
-    return Nb * OH * ((OW + 7) // 8 * 8)
+def hidet_conv2d_splitk_workspace_bytes(y_shape, k_slices):
+    """Workspace bytes of the K-parallel convolution that produces y [Nb, OC, OH, OW]."""
+    Nb, OC, OH, OW = y_shape
+    return lib().hidet_conv2d_splitk_workspace_bytes(Nb, OC, OH, OW, k_slices)
 
 
 def _ws(workspace):

@@ -437,7 +437,9 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
       }
     }
     if (slices < 0) slices = 1;
-    if (config < 0 || !find_launcher(pr, config)) config = default_config(pr, slices);
+    // (a remembered configuration that has no K-parallel form cannot serve an explicit slice count)
+    if (config < 0 || !find_launcher(pr, config) || (slices > 1 && !find_partial_launcher(pr, config)))
+      config = default_config(pr, slices);
   }
   if (slices < 0) slices = 1;
   LaunchFn fn = find_launcher(pr, config);
@@ -670,7 +672,12 @@ const TaskMapEntry kTaskMaps[] = {
     tm_entry<Compose<Spatial<1, 3>, Spatial<2, 1>>>("spatial(1,3)*spatial(2,1)"),
     tm_entry<Compose<Compose<Repeat<2, 1>, Spatial<2, 3>>, Repeat<1, 2>>>("repeat(2,1)*spatial(2,3)*repeat(1,2)"),
     tm_entry<Compose<Repeat<2, 1>, Compose<Spatial<2, 3>, Repeat<1, 2>>>>("repeat(2,1)*spatial(2,3)*repeat(1,2)"),
-    // the mappings the headline kernel (256x256x64, 8 waves) is built from
+    // the mappings the headline kernel (configuration 19: 256x256x32 tile, 8 waves, 16x16x32 matrix-core tiles) walks:
+    // its direct global -> LDS loads (Operand::init_direct) and its wave -> MFMA-tile assignment
+    tm_entry<LoadMapRowMajor<256, 4, 512>::Map>("repeat(2,1)*spatial(128,4)"),   // A tile, 256 rows x 4 chunks
+    tm_entry<LoadMapRowMajor<32, 32, 512>::Map>("repeat(2,1)*spatial(16,32)"),   // B tile, 32 k-rows x 32 chunks
+    tm_entry<Compose<Spatial<2, 4>, Repeat<8, 4>>>("spatial(2,4)*repeat(8,4)"),  // waves -> MFMA tiles
+    // the same for the general schedule on a 256x256x64 tile with 32x32x16 tiles (configuration 20)
     tm_entry<LoadMapRowMajor<256, 8, 512>::Map>("repeat(4,1)*spatial(64,8)"),    // A tile, 256 rows x 8 chunks
     tm_entry<LoadMapRowMajor<64, 32, 512>::Map>("repeat(4,1)*spatial(16,32)"),   // B tile, 64 k-rows x 32 chunks
     tm_entry<Compose<Spatial<2, 4>, Repeat<4, 2>>>("spatial(2,4)*repeat(4,2)"),  // waves -> MFMA tiles
@@ -828,6 +835,12 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
   return guarded([&] { return launch_conv(cc, config, sk, (hipStream_t)stream); });
+}
+
+int64_t hidet_conv2d_splitk_workspace_bytes(int64_t Nb, int64_t OC, int64_t OH, int64_t OW, int32_t k_slices) {
+  if (Nb < 0 || OC < 0 || OH < 0 || OW < 0 || OW > kIntMax) return -1;
+  // GEMM columns of the implicit GEMM: every output row padded to a multiple of 8 positions (see ConvGeom)
+  return hidet_splitk_workspace_bytes(1, OC, sat_mul(sat_mul(Nb, OH), (OW + 7) / 8 * 8), k_slices);
 }
 
 hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,

@@ -182,6 +182,8 @@ __device__ __forceinline__ void setup_operands(const GemmParams& p, const BlockC
   opa.K = bc.k_len;
   opa.kofs = bc.k_begin;
   opa.r0 = bc.m0;
+  opa.span = (Cfg::LA == L_KC) ? (long long)(opa.rows_left - 1) * p.lda + (p.K - bc.k_begin)
+                               : (long long)(p.K - bc.k_begin - 1) * p.lda + opa.rows_left;
   if constexpr (Cfg::MODE_B == LD_IM2COL)
     opb.src = B;  // the gather addresses the whole input tensor
   else
@@ -191,6 +193,8 @@ __device__ __forceinline__ void setup_operands(const GemmParams& p, const BlockC
   opb.K = bc.k_len;
   opb.kofs = bc.k_begin;
   opb.r0 = bc.n0;
+  opb.span = (Cfg::LB == L_KC) ? (long long)(opb.rows_left - 1) * p.ldb + (p.K - bc.k_begin)
+                               : (long long)(p.K - bc.k_begin - 1) * p.ldb + opb.rows_left;
 }
 
 // Per-column bias of the 4 columns a lane owns in the epilogue, fetched before the main loop so that

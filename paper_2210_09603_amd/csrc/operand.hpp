@@ -32,6 +32,8 @@ struct Operand {
   int K;             // extent of this workgroup's K range
   int kofs;          // global k index where that range starts (needed by the img2col gather)
   int r0;            // global row/column of the panel origin (needed by the img2col gather)
+  long long span;    // elements from `src` to the end of what the operand spans, (rows - 1) * ld + cols of one batch
+                     // entry: a 16-byte access at offset o from `src` stays inside the operand iff o + VEC <= span
 
   // ---- global -> registers ------------------------------------------------------------------
   // Element mode, a chunk of a partial K tile: rows are not 16-byte aligned (odd leading dimension, offset
@@ -48,13 +50,13 @@ struct Operand {
       if constexpr (LAYOUT == L_KC) {
         base = (long long)sr * ld + (k0 + sc);
         valid = sr < rows_left ? K - (k0 + sc) : 0;
-        // a chunk that sticks out along K is read whole and masked below, unless it ends the last row
-        whole = valid >= VEC || (valid > 0 && (kofs + k0 + sc + VEC <= ld || sr < rows_left - 1));
+        // a chunk that sticks out along K is read whole and masked below, unless it would leave the operand
+        whole = valid >= VEC || (valid > 0 && base + VEC <= span);
       } else {
         base = (long long)(k0 + sr) * ld + sc;
         valid = k0 + sr < K ? rows_left - sc : 0;
-        // a chunk that sticks out along M/N may be read whole (see init) unless it ends the last row
-        whole = valid >= VEC || (valid > 0 && (r0 + sc + VEC <= ld || k0 + sr < K - 1));
+        // a chunk that sticks out along M/N may be read whole (see init) unless it would leave the operand
+        whole = valid >= VEC || (valid > 0 && base + VEC <= span);
       }
       if (valid <= 0) return u32x4{0u, 0u, 0u, 0u};
       if (whole) {
@@ -255,7 +257,7 @@ struct Operand {
           if (rem >= VEC) {
             n = VEC;
           } else if (rem > 0) {
-            n = (r0 + sc + VEC <= ld) ? VEC : -rem;  // the padding of the row covers the over-read
+            n = -rem;
           } else {
             n = rows_left >= VEC ? VEC : 0;  // a matrix narrower than one chunk has nowhere to redirect to
             c = rows_left >= VEC ? rows_left - VEC : 0;
@@ -289,10 +291,13 @@ struct Operand {
   // several stages in flight and waits for the oldest only.
   int doff[NL];
   __device__ __forceinline__ void init_direct(int tid) {
+    static_assert(std::is_same<LoadMap, LoadMapRowMajor<SROWS, CPR, NT>>::value, "stored positions in row-major order");
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
-      const int pos = q * NT + tid;
-      const int row = pos / CPR, pc = pos % CPR;
+      // the cooperative-load task mapping repeat(NL,1) o spatial(NT/CPR, CPR): task (row, pc) of thread tid is stored
+      // position row * CPR + pc = q * NT + tid, which is where the hardware puts this lane's 16 bytes
+      const tmap::Task t = LoadMap::task(tid, q);
+      const int row = t.i, pc = t.j;
       const int lc = pc ^ ((LAYOUT == L_KC) ? swz_kc<CPR, MI>(row) : swz_mc<CPR, MI>(row));
       if constexpr (LAYOUT == L_KC) {
         const int r = row < rows_left ? row : rows_left - 1;
@@ -310,7 +315,12 @@ struct Operand {
     for (int q = 0; q < NL; ++q) {
       const T* g = base + doff[q];
       const unsigned dst = tile_lds + (unsigned)((q * NT + wave * 64) * 16);
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst) : "memory");
+      // M0 (the LDS destination of the load) is written here, so it is named as clobbered: the compiler must not
+      // keep a value of its own in it across the statement.  It reserves M0 and says so in a warning, silenced here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst) : "memory", "m0");
+#pragma clang diagnostic pop
     }
   }
 
@@ -324,8 +334,8 @@ struct Operand {
       const T* base = (LAYOUT == L_KC) ? src + k0 : src + (long long)k0 * ld;
 #pragma unroll
       for (int q = 0; q < NL; ++q) {
-        const tmap::Task t = LoadMap::task(tid, q);
-        if (nv[q] == VEC || (nv[q] < 0 && k0 + t.i < K - 1)) {
+        const long long o = ((LAYOUT == L_KC) ? (long long)k0 : (long long)k0 * ld) + eoff[q];
+        if (nv[q] == VEC || (nv[q] < 0 && o + VEC <= span)) {
           regs[q] = reinterpret_cast<const Unaligned*>(base + eoff[q])->v;
         } else {
           const int cnt = nv[q] < 0 ? -nv[q] : nv[q];

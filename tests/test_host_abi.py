@@ -326,3 +326,24 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_headline_kernel_task_mappings_are_exported():
+    """The mappings of the ring-schedule 256x256x32 configuration (its direct global -> LDS loads walk the first two,
+    its wavefronts the third) are among the exported ones, so the comparison above covers them."""
+    exprs = [hb.hidet_taskmap_info(i)["expr"] for i in range(hb.hidet_taskmap_count())]
+    for e in ("repeat(2,1)*spatial(128,4)", "repeat(2,1)*spatial(16,32)", "spatial(2,4)*repeat(8,4)"):
+        assert e in exprs
+    ring = [i for i in range(hb.hidet_config_count()) if hb.hidet_config_info(i)["schedule"] == 1]
+    big = [hb.hidet_config_info(i) for i in ring if hb.hidet_config_info(i)["block_m"] == 256 and
+           hb.hidet_config_info(i)["block_n"] == 256 and hb.hidet_config_info(i)["mfma"] == 16]
+    assert big and big[0]["block_k"] == 32 and (big[0]["waves_m"], big[0]["waves_n"]) == (2, 4)
+
+
+def test_conv_workspace_size():
+    # y [1, 24, 14, 14] in 3 slices: GEMM N pads every output row of 14 to 16 positions
+    assert hb.hidet_conv2d_splitk_workspace_bytes((1, 24, 14, 14), 3) == 4 * 3 * 24 * 14 * 16
+    assert hb.hidet_conv2d_splitk_workspace_bytes((2, 8, 7, 8), 1) == 4 * 8 * 2 * 7 * 8
+    assert hb.hidet_conv2d_splitk_workspace_bytes((1, 24, 14, 14), 3) == hb.hidet_splitk_workspace_bytes(1, 24, 14 * 16, 3)
+    assert hb.hidet_conv2d_splitk_workspace_bytes((-1, 24, 14, 14), 3) == -1
+    assert hb.hidet_conv2d_splitk_workspace_bytes((1, 24, 14, 14), 0) == -1
