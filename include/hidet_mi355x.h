@@ -39,7 +39,8 @@ typedef enum {
   HIDET_ERR_UNSUPPORTED = 2, /* dtype combination, dilation/groups, index range beyond 2^31 elements */
   HIDET_ERR_ALIGNMENT = 3,   /* pointer not aligned to its element size */
   HIDET_ERR_NO_CONFIG = 4,   /* config index out of range, or config not applicable to this problem */
-  HIDET_ERR_LAUNCH = 5       /* the HIP runtime refused the launch */
+  HIDET_ERR_LAUNCH = 5,      /* the HIP runtime refused the launch */
+  HIDET_ERR_SCRATCH = 6      /* hidet_batched_gemm_splitk_static: the partial sums do not fit the static scratch array */
 } hidet_status_t;
 
 typedef enum { HIDET_F32 = 0, HIDET_F16 = 1, HIDET_BF16 = 2 } hidet_dtype_t;
@@ -240,6 +241,24 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
  * Returns -1 under the conditions of hidet_splitk_workspace_bytes.
  */
 int64_t hidet_conv2d_splitk_workspace_bytes(int64_t Nb, int64_t OC, int64_t OH, int64_t OW, int32_t k_slices);
+/*
+ * hidet_batched_gemm_splitk for callers that cannot allocate device memory or hold a workspace of their own
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the fp32 partial sums go
+ * to a static array that is part of the library's code object -- hidet_static_scratch_bytes() = 32 MiB per GPU,
+ * held by every GPU the library runs on until the process ends.  The call allocates and frees no device memory
+ * (the array's device address is looked up once per device, on the first call with that device current); same
+ * kernels, same arguments, same results bit for bit as hidet_batched_gemm_splitk with a workspace of that size.
+ * HIDET_ERR_SCRATCH (nothing launched) if 4 * batch * effective_slices * M * N exceeds the array.  Nothing in the
+ * array needs clearing between calls: every partial tile element that the second kernel reads has been written by
+ * the first.  All calls on one GPU share the one array: calls whose execution may overlap (different streams,
+ * or the same stream from different host threads without ordering) race on it; order them on one stream.
+ */
+int64_t hidet_static_scratch_bytes(void);
+hidet_status_t hidet_batched_gemm_splitk_static(int32_t config, int32_t k_slices, int32_t in, int32_t out,
+                                                int32_t transA, int32_t transB, int64_t batch, int64_t M, int64_t N,
+                                                int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                                                int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                                                const hidet_epilogue_t* epi, void* stream);
 /*
  * Tuning over (configuration x k_slices in {1,2,3,4,6,8,12,16}) with the given workspace; slice
  * counts the workspace cannot hold are skipped.  Otherwise as hidet_tune_gemm / hidet_tune_conv2d;

@@ -59,7 +59,8 @@ EXPORTS = (
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_probe_launch_floor", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
-    "hidet_softmax_rows", "hidet_host_div", "hidet_conv2d_splitk_workspace_bytes",
+    "hidet_softmax_rows", "hidet_host_div", "hidet_conv2d_splitk_workspace_bytes", "hidet_static_scratch_bytes",
+    "hidet_batched_gemm_splitk_static",
 )
 
 _lib = None
@@ -90,6 +91,8 @@ def lib():
         L.hidet_splitk_workspace_bytes.restype = _i64
         L.hidet_conv2d_splitk_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _i32]
         L.hidet_conv2d_splitk_workspace_bytes.restype = _i64
+        L.hidet_static_scratch_bytes.restype = _i64
+        L.hidet_batched_gemm_splitk_static.argtypes = [_i32, _i32] + bgemm_args
         ws_args = [_vp, _i64, _vp]  # workspace, bytes, stream (replaces the trailing stream argument)
         L.hidet_batched_gemm_splitk.argtypes = [_i32, _i32] + bgemm_args[:-1] + ws_args
         L.hidet_conv2d_implicit_gemm_splitk.argtypes = [_i32, _i32] + conv_args[:-1] + ws_args
@@ -275,6 +278,24 @@ def hidet_conv2d_splitk_workspace_bytes(y_shape, k_slices):
     """Workspace bytes of the K-parallel convolution that produces y [Nb, OC, OH, OW]."""
     Nb, OC, OH, OW = y_shape
     return lib().hidet_conv2d_splitk_workspace_bytes(Nb, OC, OH, OW, k_slices)
+
+
+def hidet_static_scratch_bytes():
+    return lib().hidet_static_scratch_bytes()
+
+
+def hidet_batched_gemm_splitk_static(A, B, C, k_slices=0, transA=False, transB=False, epilogue=None, stream=None, config=-1):
+    """hidet_batched_gemm_splitk with the library's static scratch array as the workspace (allocates nothing)."""
+    if A.dim() == 2:
+        A, B, C = A.unsqueeze(0), B.unsqueeze(0), C.unsqueeze(0)
+    M, N, K = _gemm_dims(A, B, transA, transB)
+    batch = A.shape[0]
+    if B.shape[0] != batch or tuple(C.shape) != (batch, M, N):
+        raise ValueError("batch/shape mismatch")
+    st = lib().hidet_batched_gemm_splitk_static(config, k_slices, _dtype(A), _dtype(C), int(transA), int(transB), batch, M, N,
+                                                K, _ptr(A), _ld(A), _bstride(A), _ptr(B), _ld(B), _bstride(B), _ptr(C),
+                                                _ld(C), _bstride(C), _epi_ref(epilogue), _stream(stream))
+    _check(st, "hidet_batched_gemm_splitk_static")
 
 
 def _ws(workspace):

@@ -383,8 +383,29 @@ int default_config(const Problem& pr, int slices = 1) {
   return best >= 0 ? best : (fewer >= 0 ? fewer : most);
 }
 
+// ---- static scratch of the allocation-free K-parallel entry point --------------------------------------
+// One array per GPU, part of the code object, held until the process ends.  In host code the array's name is only
+// a handle: the device address is asked for once per device (with that device current) and kept.
+constexpr long long kScratchBytes = 32LL << 20;
+constexpr int kMaxDevices = 64;
+__device__ __attribute__((aligned(256))) unsigned char g_scratch[kScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+
 // ---- tuned-config cache ---------------------------------------------------------------------------
 std::mutex g_mutex;
+
+hidet_status_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HIDET_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_scratch)) != hipSuccess || !ptr) return HIDET_ERR_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return HIDET_OK;
+}
 struct Tuned {
   int config;
   int slices;
@@ -411,6 +432,7 @@ struct SplitK {  // how the caller wants K parallelised
   int slices = 1;            // requested number of K slices (<= 1: none); < 0 with a workspace: take the tuned value
   void* workspace = nullptr;
   long long workspace_bytes = 0;
+  bool fixed = false;  // the workspace is the library's static scratch array: too small is HIDET_ERR_SCRATCH
 };
 
 template <int MAPPER>
@@ -472,6 +494,7 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
   const long long total = sat_mul((long long)p.tiles_m * p.tiles_n, pr.batch * actual);
   if (total > kIntMax) return HIDET_ERR_UNSUPPORTED;
   const long long need = sat_mul(sat_mul(4LL * pr.batch * actual, p.M), p.N);
+  if (sk.fixed && sk.workspace_bytes < need) return HIDET_ERR_SCRATCH;
   if (!sk.workspace || sk.workspace_bytes < need) return HIDET_ERR_INVALID_ARG;
   if (!aligned(sk.workspace, 16)) return HIDET_ERR_ALIGNMENT;
   GemmParams q = p;
@@ -843,6 +866,28 @@ int64_t hidet_conv2d_splitk_workspace_bytes(int64_t Nb, int64_t OC, int64_t OH, 
   return hidet_splitk_workspace_bytes(1, OC, sat_mul(sat_mul(Nb, OH), (OW + 7) / 8 * 8), k_slices);
 }
 
+int64_t hidet_static_scratch_bytes(void) { return kScratchBytes; }
+
+hidet_status_t hidet_batched_gemm_splitk_static(int32_t config, int32_t k_slices, int32_t in, int32_t out,
+                                                int32_t transA, int32_t transB, int64_t batch, int64_t M, int64_t N,
+                                                int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
+                                                int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
+                                                const hidet_epilogue_t* epi, void* stream) {
+  Problem pr;
+  hidet_status_t st = make_gemm_problem(pr, in, out, transA, transB, batch, M, N, K, A, lda, strideA, B, ldb, strideB,
+                                        C, ldc, strideC, epi);
+  if (st != HIDET_OK) return st;
+  if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  if (k_slices > 1024) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.slices = k_slices <= 0 ? -1 : k_slices;
+  sk.workspace_bytes = kScratchBytes;
+  sk.fixed = true;
+  st = scratch_of_current_device(&sk.workspace);
+  if (st != HIDET_OK) return st;
+  return guarded([&] { return launch(pr, config, sk, (hipStream_t)stream); });
+}
+
 hidet_status_t hidet_tune_gemm_splitk(int32_t in, int32_t out, int32_t transA, int32_t transB, int64_t batch, int64_t M,
                                       int64_t N, int64_t K, const void* A, int64_t lda, int64_t strideA, const void* B,
                                       int64_t ldb, int64_t strideB, void* C, int64_t ldc, int64_t strideC,
@@ -972,6 +1017,7 @@ const char* hidet_status_string(int32_t status) {
     case HIDET_ERR_ALIGNMENT: return "misaligned pointer";
     case HIDET_ERR_NO_CONFIG: return "no applicable tile configuration";
     case HIDET_ERR_LAUNCH: return "kernel launch failed";
+    case HIDET_ERR_SCRATCH: return "partial sums exceed the static scratch array";
     default: return "unknown status";
   }
 }

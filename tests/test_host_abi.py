@@ -340,10 +340,21 @@ def test_headline_kernel_task_mappings_are_exported():
     assert big and big[0]["block_k"] == 32 and (big[0]["waves_m"], big[0]["waves_n"]) == (2, 4)
 
 
-def test_conv_workspace_size():
+def test_conv_workspace_size_and_static_scratch_limits():
+    L = hb.lib()
     # y [1, 24, 14, 14] in 3 slices: GEMM N pads every output row of 14 to 16 positions
     assert hb.hidet_conv2d_splitk_workspace_bytes((1, 24, 14, 14), 3) == 4 * 3 * 24 * 14 * 16
     assert hb.hidet_conv2d_splitk_workspace_bytes((2, 8, 7, 8), 1) == 4 * 8 * 2 * 7 * 8
     assert hb.hidet_conv2d_splitk_workspace_bytes((1, 24, 14, 14), 3) == hb.hidet_splitk_workspace_bytes(1, 24, 14 * 16, 3)
     assert hb.hidet_conv2d_splitk_workspace_bytes((-1, 24, 14, 14), 3) == -1
     assert hb.hidet_conv2d_splitk_workspace_bytes((1, 24, 14, 14), 0) == -1
+    assert hb.hidet_static_scratch_bytes() == 32 << 20
+    # argument validation of the allocation-free entry point happens before anything touches the GPU
+    args = [-1, 4, hb.HIDET_F16, hb.HIDET_F16, 0, 0, 1, 8, 8, 8, None, 8, 0, 0x2000, 8, 0, 0x3000, 8, 0, None, None]
+    assert L.hidet_batched_gemm_splitk_static(*args) == 1
+    args[10] = 0x1000
+    args[1] = 2000
+    assert L.hidet_batched_gemm_splitk_static(*args) == 1
+    args[1], args[0] = 4, 10 ** 6
+    assert L.hidet_batched_gemm_splitk_static(*args) == 4
+    assert "scratch" in L.hidet_status_string(6).decode()
