@@ -20,9 +20,13 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "f32": 157.3}  # 256 CUs x 4 SIMDs x FLOP/clk x 2.4 GHz (dense MFMA)
 
-# HBM bytes per launch of the dominant kernel at 4096^3, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
-# scaled by a plain copy of known size (profiles/gemm_pingpong_f16_4096.md); None for workloads not measured.
-MEASURED_TRAFFIC_BYTES = {("f16", 4096, 4096, 4096): 235271132}
+# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this very
+# command line, each scaled by what the same counter reads for a plain copy of known size (`--copy-calibration`).  The
+# counters cannot be read inside a timed run, so the bench line carries the figure of the committed profile together
+# with where it came from; shapes without a committed counter run report null.
+MEASURED_TRAFFIC = {
+    # (dtype, M, N, K): (bytes per launch, profile that holds the counter run)
+}
 
 
 def graph_time(torch, fn, reps=20, replays=10):
@@ -187,7 +191,7 @@ def side_report(torch, hb, wl, steps=200):
     return rows
 
 
-def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False):
+def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False, cold=False):
     """One of the secondary kernels on its own, K steps after W warm-up steps, so that a profiler sees nothing else:
     "softmax" = row softmax over the scores of the largest attention case (memory bound), "conv" = the case-study
     convolution with its tuned (tile, K-slice) choice (two kernels per step when K is sliced), "conv64" = a
@@ -199,7 +203,32 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False):
     def dev(stored):
         return torch.from_numpy(np.ascontiguousarray(stored)).cuda()
 
-    if which == "softmax":
+    if which in ("qkt", "sv"):
+        # the two attention products at batch x heads = 192, seq = 512 (the memory-bound members of the benchmark
+        # configurations): scores = Q.K^T / 8 writes 100 MB, context = S.V reads 100 MB
+        c = wl.config4("f16")[3]
+        b, sq, d = c["batch"], c["seq"], c["d"]
+        n_sets = 4 if cold else 1  # 4 x 126 MB > 256 MB
+        if which == "qkt":
+            sets = [(dev(c["Q"]), dev(c["K"]), torch.empty((b, sq, sq), dtype=torch.float16, device="cuda")) for _ in range(n_sets)]
+            epi = hb.make_epilogue(alpha=c["alpha"])
+            cfg, _ = hb.hidet_tune_gemm(*sets[0], transB=True, epilogue=epi, iters=50)
+            call = lambda t: hb.hidet_batched_gemm(t[0], t[1], t[2], transB=True, epilogue=epi, config=cfg)
+            name = "batched f16 GEMM scores = Q.K^T / 8, batch x heads = 192, seq 512, d 64 (%s)" % c["name"]
+        else:
+            sets = [(dev(c["S"]), dev(c["V"]), torch.empty((b, sq, d), dtype=torch.float16, device="cuda")) for _ in range(n_sets)]
+            cfg, _ = hb.hidet_tune_gemm(*sets[0], iters=50)
+            call = lambda t: hb.hidet_batched_gemm(t[0], t[1], t[2], config=cfg)
+            name = "batched f16 GEMM context = S.V, batch x heads = 192, seq 512, d 64 (%s)" % c["name"]
+        name += ", operands rotated over %d sets (HBM only)" % n_sets if cold else ", same buffers every launch"
+        counter = [0]
+
+        def step():
+            call(sets[counter[0] % n_sets])
+            counter[0] += 1
+        unit_bytes = (2 * b * sq * d + b * sq * sq) * 2
+        extra = {"tile_config": cfg, "k_slices": 1, "flops": 2.0 * b * sq * sq * d}
+    elif which == "softmax":
         b, s = 192, 512
         g = wl.rng(6300)
         x = dev(wl.to_storage(g.standard_normal((b * s, s)).astype(np.float32), "f16"))
@@ -434,7 +463,10 @@ def main():
     ap.add_argument("--report", default=None, metavar="PATH",
                     help="also time every parity configuration (configs 1-4 and both config-5 shapes, fp16 and bf16) "
                          "and write the table to PATH as JSON; the headline line is printed as usual")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64", "mlp", "gemm32"],
+    ap.add_argument("--cold", action="store_true",
+                    help="with --workload qkt / sv: rotate over enough copies of the operands to exceed the 256 MB Infinity "
+                         "Cache, so that every launch finds them in HBM only")
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "softmax", "conv", "conv64", "mlp", "gemm32", "qkt", "sv"],
                     help="gemm (default): the headline benchmark; softmax / conv: one secondary kernel alone (for profiling)")
     ap.add_argument("--graph-replay", action="store_true",
                     help="with --workload other than gemm: also time the call replayed from a HIP graph "
@@ -467,7 +499,7 @@ def main():
         return
 
     if args.workload != "gemm":
-        print(json.dumps(other_workload(torch, hb, wl, args.workload, args.steps, args.warmup, args.graph_replay)))
+        print(json.dumps(other_workload(torch, hb, wl, args.workload, args.steps, args.warmup, args.graph_replay, args.cold)))
         return
 
     if args.copy_calibration > 0:
@@ -517,6 +549,24 @@ def main():
     flops = 2.0 * M * N * K
     tflops = flops / (ms_per_step * 1e-3) / 1e12
 
+    # Spread of the per-launch time: a second pass of the same K launches cut into groups of consecutive launches, one
+    # HIP event between groups (an event after every single launch would add its own few microseconds to each of
+    # them); median, min and max are taken over the groups' means.
+    n_groups = min(20, args.steps)
+    per_group = max(1, args.steps // n_groups)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_groups + 1)]
+    marks[0].record(stream)
+    for g in range(n_groups):
+        for _ in range(per_group):
+            hb.hidet_gemm(A, B, C, epilogue=epi, stream=stream, config=best_cfg)
+        marks[g + 1].record(stream)
+    torch.cuda.synchronize()
+    groups = sorted(marks[g].elapsed_time(marks[g + 1]) * 1000.0 / per_group for g in range(n_groups))
+    launch_stats = {"groups": n_groups, "launches_per_group": per_group, "median_us": round(groups[n_groups // 2], 2),
+                    "min_us": round(groups[0], 2), "max_us": round(groups[-1], 2),
+                    "mean_us": round(sum(groups) / n_groups, 2),
+                    "method": "second pass, one HIP event between groups of consecutive launches"}
+
     # what the matrix cores alone sustain on these operand values (clock is power-limited and data-dependent)
     ceil_tflops, ceil_mhz = hb.hidet_probe_mfma_peak(A, mfma=cfg_info["mfma"])
     algo_bytes = (M * K + K * N + M * N + N) * 2  # every operand and the output once
@@ -544,6 +594,7 @@ def main():
             "mfma_only_ceiling_TFLOPs_same_data": round(ceil_tflops, 1),
             "mfma_only_ceiling_sclk_MHz": round(ceil_mhz),
             "pct_of_mfma_only_ceiling": round(100.0 * tflops / ceil_tflops, 2) if ceil_tflops > 0 else None,
+            "per_launch": launch_stats,
         },
         "roofline": {
             "bound": "mfma",
@@ -551,7 +602,9 @@ def main():
             "peak": PEAK_TFLOPS[dt],
             "unit": "TFLOP/s",
             "frac": round(tflops / PEAK_TFLOPS[dt], 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((dt, M, N, K)),
+            "traffic": MEASURED_TRAFFIC.get((dt, M, N, K), (None, None))[0],
+            "traffic_source": MEASURED_TRAFFIC.get((dt, M, N, K), (None, None))[1],
+            "algorithmic_bytes": algo_bytes,
         },
     }
 
