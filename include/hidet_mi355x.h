@@ -235,6 +235,35 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
                                                  const void* x, const void* w, void* y, const hidet_epilogue_t* epi,
                                                  void* workspace, int64_t workspace_bytes, void* stream);
 /*
+ * Convolution with repacked weights.  The img2col prologue (Sections 5.2 and 6.3.4) reads, for every element of the
+ * GEMM's K axis, a shifted window of the input; with the weights in OIHW order that axis is (ic, kh, kw) and every
+ * 16-byte piece of the gather has its own filter tap, padding mask and offset.  Inference weights are constants, so
+ * they can be reordered once, like the folding of batch normalisation into them: hidet_conv2d_pack_weights writes
+ * w_packed[oc][kh][kw][ic] = w[oc][ic][kh][kw] (same element count, DEVICE buffers, must not overlap, asynchronous on
+ * `stream`), and hidet_conv2d_implicit_gemm_packed computes the same convolution as hidet_conv2d_implicit_gemm from
+ * x and w_packed with the K axis ordered (kh, kw, ic): a K tile then lies within one filter tap, and mask and spatial
+ * offset are worked out once per tile instead of once per piece.  Results agree with the OIHW form to rounding
+ * (another summation order).
+ *   config, k_slices, workspace: as for hidet_conv2d_implicit_gemm_splitk; workspace may be NULL (then k_slices > 1 is
+ *     HIDET_ERR_INVALID_ARG and k_slices <= 0 means unsliced).  A configuration applies only if its block_k divides IC
+ *     (HIDET_ERR_NO_CONFIG otherwise; without an explicit configuration a fitting one is chosen).
+ *   Restrictions (HIDET_ERR_UNSUPPORTED): IC must be a multiple of 8 (fp32: 4), stride_w at most 2, w_packed 16-byte
+ *     aligned, x at least 32 elements; otherwise the limits of hidet_conv2d_implicit_gemm.
+ * hidet_tune_conv2d_packed: as hidet_tune_conv2d_splitk for the packed form (workspace may be NULL: tiles only).
+ */
+hidet_status_t hidet_conv2d_pack_weights(int32_t dtype, int64_t OC, int64_t IC, int64_t KH, int64_t KW, const void* w,
+                                         void* w_packed, void* stream);
+hidet_status_t hidet_conv2d_implicit_gemm_packed(int32_t config, int32_t k_slices, int32_t in, int32_t out, int64_t Nb,
+                                                 int64_t IC, int64_t H, int64_t W, int64_t OC, int64_t KH, int64_t KW,
+                                                 int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                                 const void* x, const void* w_packed, void* y, const hidet_epilogue_t* epi,
+                                                 void* workspace, int64_t workspace_bytes, void* stream);
+hidet_status_t hidet_tune_conv2d_packed(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W, int64_t OC,
+                                        int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                        int64_t pad_w, const void* x, const void* w_packed, void* y,
+                                        const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes, void* stream,
+                                        int32_t iters, int32_t* best_config, int32_t* best_slices, float* best_us);
+/*
  * Workspace of the K-parallel convolution (Sections 5.2 and 6.3.4: the convolution is the matrix multiplication
  * with GEMM M = OC and GEMM N = Nb*OH*roundup(OW, 8), the padded-row column order of the img2col prologue):
  * bytes that hidet_conv2d_implicit_gemm_splitk needs for an output y[Nb][OC][OH][OW] cut into k_slices.

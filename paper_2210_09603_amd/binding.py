@@ -60,7 +60,8 @@ EXPORTS = (
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_probe_launch_floor", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
     "hidet_softmax_rows", "hidet_host_div", "hidet_conv2d_splitk_workspace_bytes", "hidet_static_scratch_bytes",
-    "hidet_batched_gemm_splitk_static",
+    "hidet_batched_gemm_splitk_static", "hidet_conv2d_pack_weights", "hidet_conv2d_implicit_gemm_packed",
+    "hidet_tune_conv2d_packed",
 )
 
 _lib = None
@@ -97,6 +98,9 @@ def lib():
         L.hidet_batched_gemm_splitk.argtypes = [_i32, _i32] + bgemm_args[:-1] + ws_args
         L.hidet_conv2d_implicit_gemm_splitk.argtypes = [_i32, _i32] + conv_args[:-1] + ws_args
         tune_tail_sk = [_i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_float)]
+        L.hidet_conv2d_pack_weights.argtypes = [_i32, _i64, _i64, _i64, _i64, _vp, _vp, _vp]
+        L.hidet_conv2d_implicit_gemm_packed.argtypes = [_i32, _i32] + conv_args[:-1] + ws_args
+        L.hidet_tune_conv2d_packed.argtypes = conv_args[:-1] + ws_args + tune_tail_sk
         L.hidet_tune_gemm_splitk.argtypes = bgemm_args[:-1] + ws_args + tune_tail_sk
         L.hidet_tune_conv2d_splitk.argtypes = conv_args[:-1] + ws_args + tune_tail_sk
         L.hidet_host_div.argtypes = [_i64, _i32, ctypes.POINTER(_i32)]
@@ -330,6 +334,52 @@ def hidet_conv2d_implicit_gemm_splitk(x, w, y, workspace, k_slices=0, stride=(1,
     st = lib().hidet_conv2d_implicit_gemm_splitk(config, k_slices, *_conv_args(x, w, y, stride, pad), _epi_ref(epilogue),
                                                  wp, wb, _stream(stream))
     _check(st, "hidet_conv2d_implicit_gemm_splitk")
+
+
+def hidet_conv2d_pack_weights(w, w_packed=None, stream=None):
+    """OIHW weights -> the tap-major order [OC][KH][KW][IC] of the packed convolution; returns the packed tensor."""
+    if not w.is_contiguous():
+        raise ValueError("weights must be dense OIHW")
+    OC, IC, KH, KW = w.shape
+    if w_packed is None:
+        w_packed = torch.empty((OC, KH, KW, IC), dtype=w.dtype, device=w.device)
+    if w_packed.numel() != w.numel() or not w_packed.is_contiguous() or w_packed.dtype != w.dtype:
+        raise ValueError("w_packed must be a dense tensor of the same dtype and element count")
+    _check(lib().hidet_conv2d_pack_weights(_dtype(w), OC, IC, KH, KW, _ptr(w), _ptr(w_packed), _stream(stream)),
+           "hidet_conv2d_pack_weights")
+    return w_packed
+
+
+def _packed_conv_args(x, w_packed, y, stride, pad):
+    for t in (x, w_packed, y):
+        if not t.is_contiguous():
+            raise ValueError("conv tensors must be dense")
+    Nb, IC, H, W = x.shape
+    OC, KH, KW, IC2 = w_packed.shape
+    if IC != IC2:
+        raise ValueError("channel mismatch")
+    if tuple(y.shape) != conv_out_shape(x.shape, (OC, IC, KH, KW), stride, pad):
+        raise ValueError("y has the wrong shape")
+    return [_dtype(x), _dtype(y), Nb, IC, H, W, OC, KH, KW, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ptr(w_packed),
+            _ptr(y)]
+
+
+def hidet_conv2d_implicit_gemm_packed(x, w_packed, y, stride=(1, 1), pad=(0, 0), epilogue=None, stream=None, config=-1,
+                                      k_slices=0, workspace=None):
+    """The convolution from weights repacked by hidet_conv2d_pack_weights ([OC][KH][KW][IC])."""
+    wp, wb = _ws(workspace)
+    st = lib().hidet_conv2d_implicit_gemm_packed(config, k_slices, *_packed_conv_args(x, w_packed, y, stride, pad),
+                                                 _epi_ref(epilogue), wp, wb, _stream(stream))
+    _check(st, "hidet_conv2d_implicit_gemm_packed")
+
+
+def hidet_tune_conv2d_packed(x, w_packed, y, workspace=None, stride=(1, 1), pad=(0, 0), epilogue=None, stream=None, iters=10):
+    best, sl, us = _i32(-1), _i32(1), ctypes.c_float(0.0)
+    wp, wb = _ws(workspace)
+    st = lib().hidet_tune_conv2d_packed(*_packed_conv_args(x, w_packed, y, stride, pad), _epi_ref(epilogue), wp, wb,
+                                        _stream(stream), iters, ctypes.byref(best), ctypes.byref(sl), ctypes.byref(us))
+    _check(st, "hidet_tune_conv2d_packed")
+    return best.value, sl.value, us.value
 
 
 def hidet_tune_gemm_splitk(A, B, C, workspace, transA=False, transB=False, epilogue=None, stream=None, iters=10):

@@ -69,6 +69,7 @@ struct Problem {
   int transA = 0, transB = 0;
   long long batch = 1;
   int elem_mode = 0;  // 1: some operand is not 16-byte aligned -> element loads
+  int packed = 0;     // convolution only: 1 = weights repacked to the tap-major K order (kh, kw, ic)
   GemmParams p{};
   // conv-only key fields
   long long Nb = 0, OC = 0;
@@ -220,7 +221,7 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
   p.out_inner = 1;
   p.out_outer = 0;
   std::memset(&p.g, 0, sizeof(p.g));
-  p.g.d_khw = p.g.d_kw = p.g.d_owp = p.g.d_oh = make_fastdiv(1);
+  p.g.d_khw = p.g.d_kw = p.g.d_owp = p.g.d_oh = p.g.d_ic = make_fastdiv(1);
   return HIDET_OK;
 }
 
@@ -255,6 +256,7 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
     if (!aligned(x, es) || !aligned(w, es) || !aligned(y, es)) return HIDET_ERR_ALIGNMENT;
   }
   pr.op = 1;
+  pr.packed = 0;
   pr.dtype = in;
   pr.wide_out = 0;
   pr.transA = 0;
@@ -278,7 +280,8 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   p.strideR = 0;
   p.g = ConvGeom{(int)IC, (int)H, (int)W, (int)KH, (int)KW, (int)sh, (int)sw, (int)ph, (int)pw, (int)OH, (int)OW,
                  (int)OWP, (int)(Nb * IC * H * W), make_fastdiv(KH * KW), make_fastdiv(KW),
-                 make_fastdiv(OWP > 0 ? OWP : 1), make_fastdiv(OH > 0 ? OH : 1)};
+                 make_fastdiv(OWP > 0 ? OWP : 1), make_fastdiv(OH > 0 ? OH : 1), (int)(H * W),
+                 make_fastdiv(IC > 0 ? IC : 1)};
   p.out_inner = OH * OW;
   p.out_outer = OC * OH * OW;
   const int vec = 16 / elem_size(in);
@@ -296,6 +299,8 @@ LaunchFn find_launcher(const Problem& pr, int config) {
   if (config < 0 || config >= kNumConfigs) return nullptr;
   // The ring schedule is built without the run-time output map; a head-split problem takes the same tile's
   // general-schedule kernel (the element-mode variant, which is as fast as vector mode on aligned operands).
+  // repacked weights: the K axis is (kh, kw, ic) and a K tile must lie within one filter tap
+  if (pr.packed) return pr.p.g.IC % kConfigs[config].bk == 0 ? registry().fn[config][pr.dtype][kConvTapVariant] : nullptr;
   const int elem = (pr.p.out_map != 0 && kConfigs[config].sched == 1) ? 1 : pr.elem_mode;
   const int variant = pr.op == 1 ? conv_variant(elem) : gemm_variant(pr.transA, pr.transB, elem);
   // fp32 output from 16-bit inputs: the kernels that the K-parallel form uses for its partial sums are ordinary
@@ -306,6 +311,8 @@ LaunchFn find_launcher(const Problem& pr, int config) {
 // The fp32-output kernel of a configuration: writes the partial sums of the K-parallel form.
 LaunchFn find_partial_launcher(const Problem& pr, int config) {
   if (config < 0 || config >= kNumConfigs) return nullptr;
+  if (pr.packed)
+    return pr.p.g.IC % kConfigs[config].bk == 0 ? registry().fn[config][pr.dtype][kConvTapVariant + 1] : nullptr;
   const int variant = pr.op == 1 ? conv_variant(pr.elem_mode) : gemm_variant(pr.transA, pr.transB, pr.elem_mode);
   return registry().fn[config][pr.dtype][kPartialVariants + variant];
 }
@@ -423,8 +430,9 @@ std::string problem_key(const Problem& pr, bool with_workspace = false) {
     std::snprintf(buf, sizeof(buf), "gemm:t%d:%d%d:b%lld:%dx%dx%d:e%d:m%d", pr.dtype, pr.transA, pr.transB, pr.batch, p.M,
                   p.N, p.K, epi_kind, pr.elem_mode);
   else
-    std::snprintf(buf, sizeof(buf), "conv:t%d:n%lld:c%d:%dx%d:o%lld:k%dx%d:s%dx%d:p%dx%d:e%d:m%d", pr.dtype, pr.Nb, p.g.IC,
-                  p.g.H, p.g.W, pr.OC, p.g.KH, p.g.KW, p.g.sh, p.g.sw, p.g.ph, p.g.pw, epi_kind, pr.elem_mode);
+    std::snprintf(buf, sizeof(buf), "conv:t%d:n%lld:c%d:%dx%d:o%lld:k%dx%d:s%dx%d:p%dx%d:e%d:m%d%s", pr.dtype, pr.Nb, p.g.IC,
+                  p.g.H, p.g.W, pr.OC, p.g.KH, p.g.KW, p.g.sh, p.g.sw, p.g.ph, p.g.pw, epi_kind, pr.elem_mode,
+                  pr.packed ? ":pk" : "");
   return std::string(buf) + (with_workspace ? ":ws" : "");
 }
 
@@ -673,6 +681,37 @@ hidet_status_t tune_conv(const ConvCall& cc, const SplitK& sk, hipStream_t strea
   return HIDET_OK;
 }
 
+// ---- convolution with repacked weights ----------------------------------------------------------------------------
+// OIHW -> O(HW)I: w_packed[oc][kh][kw][ic] = w[oc][ic][kh][kw].  With the K axis of the implicit GEMM ordered
+// (kh, kw, ic) a K tile lies within one filter tap, which makes the padding mask and the spatial offset of the img2col
+// gather the same for all of a thread's chunks of the tile (Operand::request_tile).
+template <typename U>
+__global__ void __launch_bounds__(256) pack_weights_kernel(const U* __restrict__ w, U* __restrict__ wp, long long total,
+                                                          int IC, int KHW, FastDiv d_ic) {
+  const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (o >= total) return;
+  // o = (oc * KHW + t) * IC + ic; rows of KHW * IC elements stay below 2^31 (checked on the host)
+  const long long row = o / ((long long)KHW * IC);
+  const int in_row = (int)(o - row * ((long long)KHW * IC));
+  const int t = d_ic.div(in_row), ic = in_row - t * IC;
+  wp[o] = w[row * ((long long)KHW * IC) + (long long)ic * KHW + t];
+}
+
+// The packed form: a ConvCall whose gather problem is marked `packed`.  Needs IC % 8 == 0 (16-byte rows of the
+// repacked weights), strides of at most 2 and an input of at least two chunks.
+hidet_status_t make_packed_conv_call(ConvCall& cc, int in, int out, long long Nb, long long IC, long long H, long long W,
+                                     long long OC, long long KH, long long KW, long long sh, long long sw, long long ph,
+                                     long long pw, const void* x, const void* w_packed, void* y,
+                                     const hidet_epilogue_t* epi) {
+  const hidet_status_t st = make_conv_problem(cc.conv, in, out, Nb, IC, H, W, OC, KH, KW, sh, sw, ph, pw, x, w_packed, y, epi);
+  if (st != HIDET_OK) return st;
+  const int vec = 16 / elem_size(in);
+  if (IC % vec != 0 || sw > 2 || Nb * IC * H * W < 4 * vec || cc.conv.elem_mode != 0) return HIDET_ERR_UNSUPPORTED;
+  cc.conv.packed = 1;
+  cc.pointwise = false;
+  return HIDET_OK;
+}
+
 // ---- task-mapping instances exposed to tests ----------------------------------------------------------
 struct TaskMapEntry {
   const char* expr;
@@ -858,6 +897,60 @@ hidet_status_t hidet_conv2d_implicit_gemm_splitk(int32_t config, int32_t k_slice
   sk.workspace = workspace;
   sk.workspace_bytes = workspace_bytes;
   return guarded([&] { return launch_conv(cc, config, sk, (hipStream_t)stream); });
+}
+
+hidet_status_t hidet_conv2d_pack_weights(int32_t dtype, int64_t OC, int64_t IC, int64_t KH, int64_t KW, const void* w,
+                                         void* w_packed, void* stream) {
+  if (dtype < 0 || dtype > 2 || OC < 0 || IC < 0 || KH <= 0 || KW <= 0) return HIDET_ERR_INVALID_ARG;
+  if (KH > 32767 || KW > 32767 || IC > kMaxDim || OC > kMaxDim || sat_mul(IC, KH * KW) > kMaxDim) return HIDET_ERR_UNSUPPORTED;
+  const long long total = sat_mul(OC, IC * KH * KW);
+  if (total == 0) return HIDET_OK;
+  if (total > (1LL << 40)) return HIDET_ERR_UNSUPPORTED;
+  if (!w || !w_packed) return HIDET_ERR_INVALID_ARG;
+  const size_t es = (size_t)elem_size(dtype);
+  if (!aligned(w, es) || !aligned(w_packed, es)) return HIDET_ERR_ALIGNMENT;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (es == 2)
+    hipLaunchKernelGGL(pack_weights_kernel<unsigned short>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const unsigned short*)w, (unsigned short*)w_packed, total, (int)IC, (int)(KH * KW), make_fastdiv(IC));
+  else
+    hipLaunchKernelGGL(pack_weights_kernel<unsigned int>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const unsigned int*)w, (unsigned int*)w_packed, total, (int)IC, (int)(KH * KW), make_fastdiv(IC));
+  return hipGetLastError() == hipSuccess ? HIDET_OK : HIDET_ERR_LAUNCH;
+}
+
+hidet_status_t hidet_conv2d_implicit_gemm_packed(int32_t config, int32_t k_slices, int32_t in, int32_t out, int64_t Nb,
+                                                 int64_t IC, int64_t H, int64_t W, int64_t OC, int64_t KH, int64_t KW,
+                                                 int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                                 const void* x, const void* w_packed, void* y, const hidet_epilogue_t* epi,
+                                                 void* workspace, int64_t workspace_bytes, void* stream) {
+  ConvCall cc;
+  hidet_status_t st = make_packed_conv_call(cc, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x,
+                                            w_packed, y, epi);
+  if (st != HIDET_OK) return st;
+  if (config >= kNumConfigs) return HIDET_ERR_NO_CONFIG;
+  if (workspace_bytes < 0 || k_slices > 1024) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.slices = k_slices <= 0 ? (workspace ? -1 : 1) : k_slices;
+  sk.workspace = workspace;
+  sk.workspace_bytes = workspace_bytes;
+  return guarded([&] { return launch(cc.conv, config, sk, (hipStream_t)stream); });
+}
+
+hidet_status_t hidet_tune_conv2d_packed(int32_t in, int32_t out, int64_t Nb, int64_t IC, int64_t H, int64_t W, int64_t OC,
+                                        int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                        int64_t pad_w, const void* x, const void* w_packed, void* y,
+                                        const hidet_epilogue_t* epi, void* workspace, int64_t workspace_bytes, void* stream,
+                                        int32_t iters, int32_t* best_config, int32_t* best_slices, float* best_us) {
+  ConvCall cc;
+  hidet_status_t st = make_packed_conv_call(cc, in, out, Nb, IC, H, W, OC, KH, KW, stride_h, stride_w, pad_h, pad_w, x,
+                                            w_packed, y, epi);
+  if (st != HIDET_OK) return st;
+  if (workspace_bytes < 0) return HIDET_ERR_INVALID_ARG;
+  SplitK sk;
+  sk.workspace = workspace;
+  sk.workspace_bytes = workspace ? workspace_bytes : 0;
+  return guarded([&] { return tune(cc.conv, sk, (hipStream_t)stream, iters, best_config, best_slices, best_us); });
 }
 
 int64_t hidet_conv2d_splitk_workspace_bytes(int64_t Nb, int64_t OC, int64_t OH, int64_t OW, int32_t k_slices) {

@@ -39,7 +39,8 @@ struct GemmConfig {
   // partial accumulators of the wave groups 1 .. WAVES_K-1, behind the epilogue regions
   static constexpr int RED_BYTES = (WAVES_K - 1) * NWAVES_MN * 64 * (FM * FN * MI * MI / 64) * 4;
   // img2col gather: table of the 16-byte masks that keep elements [lo, hi) of a chunk, behind the stages
-  static constexpr int MASK_BYTES = (MODE_B == LD_IM2COL) ? (VEC + 1) * (VEC + 1) * 16 : 0;
+  static constexpr bool GATHER_B = MODE_B == LD_IM2COL || MODE_B == LD_IM2COL_TAP;
+  static constexpr int MASK_BYTES = GATHER_B ? (VEC + 1) * (VEC + 1) * 16 : 0;
   static constexpr int MAIN_BYTES = STAGES * STAGE_BYTES + MASK_BYTES;
   static constexpr int LDS_BYTES = MAIN_BYTES > EPI_BYTES + RED_BYTES ? MAIN_BYTES : EPI_BYTES + RED_BYTES;
   static constexpr int NL_A = BM * BK / VEC / NT;  // chunks per thread per tile

@@ -184,7 +184,7 @@ __device__ __forceinline__ void setup_operands(const GemmParams& p, const BlockC
   opa.r0 = bc.m0;
   opa.span = (Cfg::LA == L_KC) ? (long long)(opa.rows_left - 1) * p.lda + (p.K - bc.k_begin)
                                : (long long)(p.K - bc.k_begin - 1) * p.lda + opa.rows_left;
-  if constexpr (Cfg::MODE_B == LD_IM2COL)
+  if constexpr (Cfg::GATHER_B)
     opb.src = B;  // the gather addresses the whole input tensor
   else
     opb.src = (Cfg::LB == L_KC) ? B + (long long)bc.n0 * p.ldb + bc.k_begin : B + (long long)bc.k_begin * p.ldb + bc.n0;

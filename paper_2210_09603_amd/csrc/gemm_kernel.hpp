@@ -85,7 +85,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
   u32x4 ra[OpA::NL], rb[OpB::NL];
   opa.init(tid, p.g);
   opb.init(tid, p.g);
-  if constexpr (Cfg::MODE_B == LD_IM2COL) {
+  if constexpr (Cfg::GATHER_B) {
     opb.fill_masks(tid, smem + Cfg::STAGES * Cfg::STAGE_BYTES);
     __syncthreads();
   }

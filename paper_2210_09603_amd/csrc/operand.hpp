@@ -115,12 +115,20 @@ struct Operand {
   // A chunk is fetched in two phases so that the loads of all of a thread's chunks -- and the matrix-core work of
   // the current tile -- overlap their latency: request_window() forms the address and issues the load(s),
   // finish_window(), called when the tile is written to LDS, applies what depends on the loaded value.
-  static constexpr int NP = (MODE == LD_IM2COL) ? NL : 1;
+  static constexpr bool GATHER = MODE == LD_IM2COL || MODE == LD_IM2COL_TAP;
+  static constexpr int NP = GATHER ? NL : 1;
   u32x4 win2[NP];  // stride 2: the second half of the window
   u32x4 wmask[NP]; // the 16-byte mask that keeps elements [lo, hi)
   int wstart[NP];  // element offset of the window
   int winfo[NP];   // lo * (VEC + 1) + hi: elements [lo, hi) are kept; bit 8: the window leaves the tensor
   int wsw;         // 2: windows are 2 * VEC elements of which the even ones are used; else 1
+  // Tap-major K order (LD_IM2COL_TAP): a K tile lies within one filter tap, so everything that depends on the tap
+  // and on the thread's output positions -- the kept range [lo, hi), its mask, the spatial part of the window's
+  // offset -- is the same for all of the thread's chunks of the tile and is worked out once per tile; a chunk then
+  // costs one multiply-add for its channel, a bounds test and the load.
+  u32x4 tmask;     // mask of the current tile
+  int tinfo;       // lo * (VEC + 1) + hi of the current tile
+  unsigned tedge;  // bit q: chunk q's window leaves the tensor (first or last pixels), fetched element-wise at the store
   // LDS table of 16-byte masks: entry lo * (VEC + 1) + hi keeps elements [lo, hi) of a chunk
   const unsigned char* masks;
   static constexpr int MASK_ENTRIES = (VEC + 1) * (VEC + 1);
@@ -180,6 +188,39 @@ struct Operand {
     return gather_elements(start, step, [=](int e) { return e < cnt && (unsigned)(iwf + e * step) < (unsigned)W; });
   }
 
+  // Tap-major gather: requests all chunks of the K tile that starts at k0 (k = (kh * KW + kw) * IC + ic; the host
+  // guarantees IC % BK == 0, strides of at most 2 and a tensor of at least two chunks).
+  __device__ __forceinline__ void request_tile(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) {
+    const int kt0 = kofs + k0;
+    const int tap = g.d_ic.div(kt0), ic0 = kt0 - tap * g.IC;  // uniform over the workgroup
+    const int kh = g.d_kw.div(tap), kw = tap - kh * g.KW;
+    const int ih = ih0 + kh, iwf = iw0 + kw;
+    const int sw = g.sw, sft = sw - 1;
+    int lo = (sft - iwf) >> sft;
+    int hi = ((g.W - 1 - iwf) >> sft) + 1;
+    lo = lo < 0 ? 0 : (lo > VEC ? VEC : lo);
+    hi = hi < 0 ? 0 : (hi > pcnt ? pcnt : hi);
+    if ((unsigned)ih >= (unsigned)g.H) hi = 0;
+    const bool any = hi > lo;
+    tinfo = lo * (VEC + 1) + hi;
+    tmask = *reinterpret_cast<const u32x4*>(masks + tinfo * 16);
+    wsw = sw;
+    tedge = 0u;
+    const unsigned base = (unsigned)pofs + (unsigned)(kh * g.W + kw) + (unsigned)ic0 * (unsigned)g.HW;
+    const int last = g.numel_x - VEC * sw;
+#pragma unroll
+    for (int q = 0; q < NL; ++q) {
+      const int sr = LoadMap::task(tid, q).i;  // channel of the chunk within the tile
+      const int start = (int)(base + (unsigned)sr * (unsigned)g.HW);
+      const bool inside = start >= 0 && start <= last;
+      const T* win = src + ((any && inside) ? start : 0);
+      wstart[q] = start;
+      if (any && !inside) tedge |= 1u << q;
+      if (sw == 2) win2[q] = reinterpret_cast<const Unaligned*>(win + VEC)->v;
+      regs[q] = reinterpret_cast<const Unaligned*>(win)->v;
+    }
+  }
+
   // The rare forms of the gather (strides above 2, windows at the very ends of the tensor): a rolled loop of
   // predicated single-element loads, small in code and registers because it is off the hot path.
   template <class Pred>
@@ -206,6 +247,24 @@ struct Operand {
   }
 
   __device__ __forceinline__ u32x4 finish_window(int q, u32x4 v) const {
+    if constexpr (MODE == LD_IM2COL_TAP) {
+      if (wsw == 2) {
+        const u32x4 w = win2[q];
+        if constexpr (IS_F32) {
+          v = u32x4{v[0], v[2], w[0], w[2]};
+        } else {
+          v = u32x4{(v[0] & 0xffffu) | (v[1] << 16), (v[2] & 0xffffu) | (v[3] << 16),
+                    (w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] &= tmask[i];
+      if (tedge & (1u << q)) {
+        const int lo = tinfo / (VEC + 1), hi = tinfo % (VEC + 1);
+        v = gather_elements(wstart[q], wsw, [=](int e) { return e >= lo && e < hi; });
+      }
+      return v;
+    }
     const int info = winfo[q];
     if (wsw == 2) {
       const u32x4 w = win2[q];
@@ -228,7 +287,7 @@ struct Operand {
   }
 
   __device__ __forceinline__ void init(int tid, const ConvGeom& g) {
-    if constexpr (MODE == LD_IM2COL) {
+    if constexpr (GATHER) {
       static_assert(std::is_same<LoadMap, LoadMapRowMajor<SROWS, CPR, NT>>::value, "one chunk column per thread");
       const int sc = LoadMap::task(tid, 0).j * VEC;
       const int p = r0 + sc;                             // GEMM column of element 0
@@ -356,6 +415,10 @@ struct Operand {
 
   // The last, partial K tile (and every tile of the element-wise modes).
   __device__ __forceinline__ void load_edge(u32x4 (&regs)[NL], int tid, int k0, const ConvGeom& g) {
+    if constexpr (MODE == LD_IM2COL_TAP) {
+      request_tile(regs, tid, k0, g);
+      return;
+    }
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
@@ -380,7 +443,7 @@ struct Operand {
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
       u32x4 v = regs[q];
-      if constexpr (MODE == LD_IM2COL) v = finish_window(q, v);
+      if constexpr (GATHER) v = finish_window(q, v);
       if constexpr (!IS_F32) {
         const int swz = (LAYOUT == L_KC) ? swz_kc<CPR, MI>(t.i) : swz_mc<CPR, MI>(t.i);
         *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = v;

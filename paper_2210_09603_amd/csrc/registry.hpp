@@ -11,9 +11,10 @@ using LaunchFn = hipError_t (*)(const GemmParams&, hipStream_t);
 
 constexpr int kMaxConfigs = 64;
 constexpr int kNumTypes = 3;     // index = hidet_dtype_t of the inputs: 0 f32, 1 f16, 2 bf16 (output has the same type)
-constexpr int kNumVariants = 20; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode;
+constexpr int kNumVariants = 22; // GEMM: transA*4 + transB*2 + mode (0 vector loads, 1 element loads); conv: 8 + mode;
                                  // +10: the same operand forms writing raw fp32 partial sums to a plain [M][N]
-                                 // workspace (first pass of the parallel reduction on K)
+                                 // workspace (first pass of the parallel reduction on K);
+                                 // 20, 21: convolution with repacked (tap-major) weights, and its partial-sum form
 
 struct ConfigRow {
   int index, bm, bn, bk, waves_m, waves_n, mfma, trans_a, sched, is_f32;
@@ -26,6 +27,7 @@ struct Registry {
 inline int gemm_variant(int transA, int transB, int elem_mode) { return (transA ? 4 : 0) + (transB ? 2 : 0) + (elem_mode ? 1 : 0); }
 inline int conv_variant(int elem_mode) { return 8 + (elem_mode ? 1 : 0); }
 constexpr int kPartialVariants = 10;  // offset of the K-parallel partial-sum kernels
+constexpr int kConvTapVariant = 20;   // convolution over the tap-major K order (repacked weights); +1: partial sums
 
 template <class Cfg>
 hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
@@ -63,6 +65,7 @@ void register_config(Registry& r, int index, int type_index) {
   // convolution: weights are a row-major OC x (IC*KH*KW) matrix, B is the img2col gather, C is NCHW
   v[conv_variant(0)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_NCHW, GS>>;
   v[conv_variant(1)] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_NCHW, GS>>;
+  v[kConvTapVariant] = launch_kernel<GemmConfig<T, T, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL_TAP, MAP_NCHW, GS>>;
   // K-parallel partial sums (fp32 out, plain map): built for the small and medium tiles, which are the ones a
   // problem with few output tiles and a long K wants, and for the ring-schedule tiles (medium-sized problems whose
   // tiles do not fill the device)
@@ -80,6 +83,7 @@ void register_config(Registry& r, int index, int type_index) {
     }
     w[conv_variant(0)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL, MAP_PLAIN, GS>>;
     w[conv_variant(1)] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_ELEM, LD_IM2COL, MAP_PLAIN, GS>>;
+    v[kConvTapVariant + 1] = launch_kernel<GemmConfig<T, float, BM, BN, BK, WM, WN, MI, L_KC, L_MC, LD_VEC, LD_IM2COL_TAP, MAP_PLAIN, GS>>;
   }
 }
 

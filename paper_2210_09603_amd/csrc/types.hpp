@@ -22,7 +22,9 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 enum : int { L_KC = 0, L_MC = 1 };                    // operand contiguity
-enum : int { LD_VEC = 0, LD_ELEM = 1, LD_IM2COL = 2 };  // how a chunk is fetched from global memory
+// how a chunk is fetched from global memory; LD_IM2COL_TAP is the img2col gather over a K axis ordered (kh, kw, ic)
+// with ic fastest (weights repacked to match), so that a K tile lies within one filter tap
+enum : int { LD_VEC = 0, LD_ELEM = 1, LD_IM2COL = 2, LD_IM2COL_TAP = 3 };
 enum : int { MAP_PLAIN = 0, MAP_NCHW = 1 };           // output index map
 enum : int { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1, SCHED_AHEAD = 2, SCHED_KSPLIT = 3 };  // main-loop schedule
 
@@ -61,6 +63,8 @@ struct ConvGeom {
   int IC, H, W, KH, KW, sh, sw, ph, pw, OH, OW, OWP;
   int numel_x;                         // elements of the input tensor (bounds of the whole-chunk loads)
   FastDiv d_khw, d_kw, d_owp, d_oh;    // dividers by KH*KW, KW, OWP, OH
+  int HW;                              // H * W
+  FastDiv d_ic;                        // divider by IC (tap-major K order: k = (kh * KW + kw) * IC + ic)
 };
 
 struct GemmParams {

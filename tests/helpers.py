@@ -151,17 +151,23 @@ def run_gemm_case(c, config=-1, relu=None, alpha=None, k_slices=None):
     return oracle.rel_frobenius(got, ref), got, ref
 
 
-def run_conv_case(c, config=-1, k_slices=None):
+def run_conv_case(c, config=-1, k_slices=None, packed=False):
+    """Run one workloads.conv_case through the HIP path and the oracle.  packed=True: the weights are repacked by
+    hidet_conv2d_pack_weights and the packed entry point runs (the oracle always sees the OIHW weights)."""
     dt = c["dtype"]
     x, w = to_gpu(c["x"], dt), to_gpu(c["w"], dt)
     bias, res = to_gpu(c["bias"], dt), to_gpu(c["residual"], dt)
-    stride, pad = (c["stride"], c["stride"]), (c["pad"], c["pad"])
-    if isinstance(c["stride"], tuple):
-        stride, pad = c["stride"], c["pad"]
+    stride = c["stride"] if isinstance(c["stride"], tuple) else (c["stride"], c["stride"])
+    pad = c["pad"] if isinstance(c["pad"], tuple) else (c["pad"], c["pad"])
     y = torch.full(hb.conv_out_shape(x.shape, w.shape, stride, pad), float("nan"), dtype=TORCH_DTYPE[dt], device="cuda")
     epi = hb.make_epilogue(alpha=c.get("alpha", 1.0), bias=bias, bias_axis=hb.HIDET_BIAS_PER_ROW, residual=res,
                            relu=c.get("relu", False))
-    if k_slices is None:
+    if packed:
+        wp = hb.hidet_conv2d_pack_weights(w)
+        ws = None if k_slices is None else make_conv_workspace(y.shape, k_slices)
+        hb.hidet_conv2d_implicit_gemm_packed(x, wp, y, stride=stride, pad=pad, epilogue=epi, config=config,
+                                             k_slices=k_slices or 0, workspace=ws)
+    elif k_slices is None:
         hb.hidet_conv2d_implicit_gemm(x, w, y, stride=stride, pad=pad, epilogue=epi, config=config)
     else:
         ws = make_conv_workspace(y.shape, k_slices)

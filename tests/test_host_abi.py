@@ -358,3 +358,31 @@ def test_conv_workspace_size_and_static_scratch_limits():
     args[1], args[0] = 4, 10 ** 6
     assert L.hidet_batched_gemm_splitk_static(*args) == 4
     assert "scratch" in L.hidet_status_string(6).decode()
+
+
+def test_packed_conv_argument_validation():
+    L = hb.lib()
+    INVALID, UNSUPPORTED, ALIGN, NOCFG = 1, 2, 3, 4
+    assert L.hidet_conv2d_pack_weights(hb.HIDET_F16, 8, 8, 3, 3, None, 0x2000, None) == INVALID
+    assert L.hidet_conv2d_pack_weights(hb.HIDET_F16, 8, 8, 0, 3, 0x1000, 0x2000, None) == INVALID
+    assert L.hidet_conv2d_pack_weights(7, 8, 8, 3, 3, 0x1000, 0x2000, None) == INVALID
+    assert L.hidet_conv2d_pack_weights(hb.HIDET_F16, 8, 8, 3, 3, 0x1001, 0x2000, None) == ALIGN
+    assert L.hidet_conv2d_pack_weights(hb.HIDET_F16, 0, 8, 3, 3, None, None, None) == 0  # nothing to do
+
+    def packed(**kw):
+        a = dict(config=-1, slices=0, i=hb.HIDET_F16, o=hb.HIDET_F16, Nb=1, IC=16, H=8, W=8, OC=8, KH=3, KW=3, sh=1, sw=1,
+                 ph=1, pw=1, x=0x1000, w=0x2000, y=0x3000, epi=None, ws=None, wsb=0, stream=None)
+        a.update(kw)
+        return L.hidet_conv2d_implicit_gemm_packed(a["config"], a["slices"], a["i"], a["o"], a["Nb"], a["IC"], a["H"], a["W"],
+                                                   a["OC"], a["KH"], a["KW"], a["sh"], a["sw"], a["ph"], a["pw"], a["x"],
+                                                   a["w"], a["y"], a["epi"], a["ws"], a["wsb"], a["stream"])
+    assert packed(x=None) == INVALID
+    assert packed(IC=12) == UNSUPPORTED          # rows of the repacked weights must be 16-byte multiples
+    assert packed(sw=3) == UNSUPPORTED
+    assert packed(w=0x2002) == UNSUPPORTED       # the packed weights are read with 16-byte loads
+    assert packed(slices=2000) == INVALID
+    assert packed(config=10 ** 6) == NOCFG
+    # a tile whose K extent does not divide IC cannot keep a K tile within one filter tap
+    cfgs = [i for i in range(hb.hidet_config_count()) if not hb.hidet_config_info(i)["is_f32"]
+            and 16 % hb.hidet_config_info(i)["block_k"] != 0]
+    assert cfgs and packed(config=cfgs[0]) == NOCFG
