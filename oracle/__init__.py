@@ -98,6 +98,15 @@ def _make_epilogue(alpha, bias, bias_axis, residual, relu, keep):
     return ctypes.byref(e)
 
 
+def input_relu(x):
+    """The fused input prologue (Section 5.2: a prologue replaces every access X[i] of an input of the anchor
+    operator by f(X[i]); its example scales the accessed element): here f is the ReLU that precedes a matmul or a
+    convolution in a network, f(v) = 0 for v < 0, else v.  Every access is replaced, so applying f to the whole
+    operand first is the same computation -- which is what the unfused graph does."""
+    x = _f64(x)
+    return np.where(x < 0.0, 0.0, x)
+
+
 def _check_bias(bias, bias_axis, M, N):
     if bias is not None:
         want = N if bias_axis == BIAS_PER_COL else M
@@ -106,12 +115,15 @@ def _check_bias(bias, bias_axis, M, N):
 
 
 def gemm(A, B, transA=False, transB=False, alpha=1.0, bias=None, bias_axis=BIAS_PER_COL, residual=None, relu=False,
-         rows=None):
+         rows=None, relu_input=False):
     """C = Epi(op(A) . op(B)) in float64.  A is stored [M,K] ([K,M] if transA); B [K,N] ([N,K] if transB).
 
     ``rows=(r0, r1)`` computes only that row range (the rest of the returned array is zero).
+    ``relu_input``: the input prologue on the activation operand A (see input_relu).
     """
     A, B = _f64(A), _f64(B)
+    if relu_input:
+        A = input_relu(A)
     M, K = (A.shape[1], A.shape[0]) if transA else A.shape
     Kb, N = (B.shape[1], B.shape[0]) if transB else B.shape
     if K != Kb:
@@ -144,9 +156,11 @@ def gemm_element(A, B, i, j, transA=False, transB=False, alpha=1.0, bias=None, b
 
 
 def batched_gemm(A, B, transA=False, transB=False, alpha=1.0, bias=None, bias_axis=BIAS_PER_COL, residual=None,
-                 relu=False):
+                 relu=False, relu_input=False):
     """Independent GEMMs over the leading batch axis of A [b,..], B [b,..] (and residual [b,M,N])."""
     A, B = _f64(A), _f64(B)
+    if relu_input:
+        A = input_relu(A)
     batch = A.shape[0]
     if B.shape[0] != batch:
         raise ValueError("batch sizes differ")
@@ -173,9 +187,12 @@ def conv_out_size(H, KH, stride, pad):
     return (H + 2 * pad - KH) // stride + 1
 
 
-def conv2d(x, w, stride=(1, 1), pad=(0, 0), alpha=1.0, bias=None, residual=None, relu=False):
-    """Direct NCHW convolution (cross-correlation, zero padding) with per-output-channel bias, in float64."""
+def conv2d(x, w, stride=(1, 1), pad=(0, 0), alpha=1.0, bias=None, residual=None, relu=False, relu_input=False):
+    """Direct NCHW convolution (cross-correlation, zero padding) with per-output-channel bias, in float64.
+    ``relu_input``: the input prologue on the activation operand x (see input_relu)."""
     x, w = _f64(x), _f64(w)
+    if relu_input:
+        x = input_relu(x)
     Nb, IC, H, W = x.shape
     OC, IC2, KH, KW = w.shape
     if IC != IC2:

@@ -295,6 +295,46 @@ def test_conv_alpha_scales_the_sum_before_bias_residual_and_relu(alpha, flags):
     assert np.array_equal(y, v)
 
 
+# ---------------------------------------------------------------- input prologue
+def test_input_prologue_relu_on_the_activation_operand():
+    """Section 5.2: a fused prologue replaces every access of an input by f(access); f = ReLU on A (GEMM) or x (conv)."""
+    # closed forms: a non-positive activation contributes nothing, a non-negative one is untouched
+    M, N, K = 4, 5, 6
+    bias = np.arange(N, dtype=np.float64) - 1.5
+    C = oracle.gemm(-np.ones((M, K)), np.ones((K, N)), bias=bias, relu_input=True)
+    assert np.array_equal(C, np.broadcast_to(bias, (M, N)))
+    C = oracle.gemm(np.ones((M, K)), -np.ones((K, N)), relu_input=True)  # only A passes through f, B does not
+    assert np.array_equal(C, np.full((M, N), -float(K)))
+    A = np.array([[1.0, -2.0, 3.0, -4.0]])
+    assert oracle.gemm(A, np.ones((4, 1)), relu_input=True)[0, 0] == 4.0   # 1 + 3
+    assert oracle.gemm(A, np.ones((4, 1)), relu_input=False)[0, 0] == -2.0
+    # exact rationals on integer data, all transposes, with an epilogue behind it
+    g = np.random.default_rng(31)
+    for transA in (False, True):
+        for transB in (False, True):
+            A = g.integers(-5, 6, size=(4, 3) if transA else (3, 4)).astype(np.float64)
+            B = g.integers(-5, 6, size=(5, 4) if transB else (4, 5)).astype(np.float64)
+            res = g.integers(-9, 10, size=(3, 5)).astype(np.float64)
+            got = oracle.gemm(A, B, transA=transA, transB=transB, alpha=0.5, residual=res, relu=True, relu_input=True)
+            Ap = [[max(int(v), 0) for v in row] for row in A]
+            want = _exact_gemm(Ap, B, transA, transB, 0.5, None, BIAS_PER_COL, res, True)
+            for i in range(3):
+                for j in range(5):
+                    assert Fraction(float(got[i, j])) == want[i][j]
+    # a library routine: numpy's maximum and matmul in float64
+    A, B = g.standard_normal((9, 17)), g.standard_normal((17, 8))
+    assert oracle.rel_frobenius(oracle.gemm(A, B, relu_input=True), np.maximum(A, 0.0) @ B) < 1e-15
+    Ab, Bb = g.standard_normal((3, 4, 6)), g.standard_normal((3, 6, 5))
+    assert oracle.rel_frobenius(oracle.batched_gemm(Ab, Bb, relu_input=True), np.maximum(Ab, 0.0) @ Bb) < 1e-15
+    # convolution: the activation is x; padding stays zero; torch in float64
+    x, w = g.standard_normal((2, 3, 6, 5)), g.standard_normal((4, 3, 3, 3))
+    y = oracle.conv2d(x, w, pad=(1, 1), relu_input=True)
+    ref = torch.nn.functional.conv2d(torch.relu(torch.from_numpy(x)), torch.from_numpy(w), padding=1).numpy()
+    assert oracle.rel_frobenius(y, ref) < 1e-14
+    assert np.array_equal(oracle.conv2d(-np.abs(x), w, pad=(1, 1), bias=np.arange(4.0), relu_input=True),
+                          np.broadcast_to(np.arange(4.0)[None, :, None, None], (2, 4, 6, 5)))
+
+
 # ---------------------------------------------------------------- the error measure itself
 def test_rel_frobenius():
     ref = np.array([[3.0, 4.0]])
