@@ -47,6 +47,7 @@ typedef enum { HIDET_F32 = 0, HIDET_F16 = 1, HIDET_BF16 = 2 } hidet_dtype_t;
 typedef enum { HIDET_BIAS_NONE = 0, HIDET_BIAS_PER_COL = 1 /* length N */, HIDET_BIAS_PER_ROW = 2 /* length M */ } hidet_bias_axis_t;
 typedef enum { HIDET_ACT_NONE = 0, HIDET_ACT_RELU = 1 } hidet_act_t;
 typedef enum { HIDET_MAP_PLAIN = 0, HIDET_MAP_HEAD_SPLIT = 1 } hidet_out_map_t;
+typedef enum { HIDET_PROLOGUE_NONE = 0, HIDET_PROLOGUE_RELU = 1 } hidet_prologue_t;
 
 /*
  * Fused epilogue: the elementwise ("bijective") operators that post-scheduling fusion folds into
@@ -68,6 +69,13 @@ typedef enum { HIDET_MAP_PLAIN = 0, HIDET_MAP_HEAD_SPLIT = 1 } hidet_out_map_t;
  * tensor of that same shape, bias still follows the GEMM index (per column j or per row i).
  * Only for hidet_gemm* and batch == 1 (HIDET_ERR_UNSUPPORTED otherwise); map_seq must divide M and
  * map_head_dim must divide N (HIDET_ERR_INVALID_ARG otherwise).
+ *
+ * prologue is the other direction of post-scheduling fusion (Section 5.2: a fused prologue replaces every access
+ * X[i] of an input of the anchor operator by f(X[i])) and travels in this descriptor because it describes the same
+ * fused sub-graph.  HIDET_PROLOGUE_RELU applies f(v) = (v < 0 ? 0 : v) to every element of the ACTIVATION operand as
+ * it is loaded -- A of the GEMMs, x of the convolution (a ReLU that precedes the matmul / convolution in the
+ * network); the weights (B, w) are not touched, padding stays zero.  With it, tile configurations whose loads
+ * bypass the registers run their through-registers form.
  */
 typedef struct {
   uint32_t struct_size;
@@ -79,7 +87,7 @@ typedef struct {
   int64_t ld_residual;
   int64_t batch_stride_residual;
   int32_t out_map; /* hidet_out_map_t */
-  int32_t reserved; /* must be 0 */
+  int32_t prologue; /* hidet_prologue_t: fused prologue of the activation operand, see above */
   int64_t map_seq;
   int64_t map_head_dim;
 } hidet_epilogue_t;

@@ -17,6 +17,7 @@ HIDET_F32, HIDET_F16, HIDET_BF16 = 0, 1, 2
 HIDET_BIAS_NONE, HIDET_BIAS_PER_COL, HIDET_BIAS_PER_ROW = 0, 1, 2
 HIDET_ACT_NONE, HIDET_ACT_RELU = 0, 1
 HIDET_MAP_PLAIN, HIDET_MAP_HEAD_SPLIT = 0, 1
+HIDET_PROLOGUE_NONE, HIDET_PROLOGUE_RELU = 0, 1
 HIDET_REDUCE_SUM, HIDET_REDUCE_MAX, HIDET_REDUCE_MEAN = 0, 1, 2
 
 _DTYPES = {torch.float32: HIDET_F32, torch.float16: HIDET_F16, torch.bfloat16: HIDET_BF16}
@@ -35,7 +36,7 @@ class hidet_epilogue_t(ctypes.Structure):
         ("ld_residual", _i64),
         ("batch_stride_residual", _i64),
         ("out_map", _i32),
-        ("reserved", _i32),
+        ("prologue", _i32),
         ("map_seq", _i64),
         ("map_head_dim", _i64),
     ]
@@ -154,11 +155,12 @@ def _ld(t):
 
 
 def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None, relu=False, batched=False,
-                  head_split=None):
+                  head_split=None, relu_input=False):
     """Build a hidet_epilogue_t (returns None for the identity epilogue).  head_split=(seq, head_dim) selects the
     [b][h][s][f] output index map; the residual (if any) is then a dense tensor of that shape.  A 3-D residual
-    advances by its own batch stride (`batched` is accepted for older callers and ignored)."""
-    if alpha == 1.0 and bias is None and residual is None and not relu and head_split is None:
+    advances by its own batch stride (`batched` is accepted for older callers and ignored).  relu_input: the fused
+    prologue, ReLU on the activation operand (A of a GEMM, x of a convolution) as it is loaded."""
+    if alpha == 1.0 and bias is None and residual is None and not relu and head_split is None and not relu_input:
         return None
     e = hidet_epilogue_t()
     e.struct_size = ctypes.sizeof(hidet_epilogue_t)
@@ -169,6 +171,7 @@ def make_epilogue(alpha=1.0, bias=None, bias_axis=HIDET_BIAS_NONE, residual=None
     e.bias = bias.data_ptr() if bias is not None else None
     e.bias_axis = bias_axis if bias is not None else HIDET_BIAS_NONE
     e.act = HIDET_ACT_RELU if relu else HIDET_ACT_NONE
+    e.prologue = HIDET_PROLOGUE_RELU if relu_input else HIDET_PROLOGUE_NONE
     if head_split is not None:
         e.out_map = HIDET_MAP_HEAD_SPLIT
         e.map_seq, e.map_head_dim = head_split

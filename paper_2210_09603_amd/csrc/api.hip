@@ -112,7 +112,7 @@ hidet_status_t check_epilogue(const hidet_epilogue_t* epi, int dtype, bool conv)
   if (epi->bias_axis < 0 || epi->bias_axis > 2 || epi->act < 0 || epi->act > 1) return HIDET_ERR_INVALID_ARG;
   if (epi->bias_axis != HIDET_BIAS_NONE && !epi->bias) return HIDET_ERR_INVALID_ARG;
   if (conv && epi->bias_axis == HIDET_BIAS_PER_COL) return HIDET_ERR_INVALID_ARG;
-  if (epi->out_map < 0 || epi->out_map > 1 || epi->reserved != 0) return HIDET_ERR_INVALID_ARG;
+  if (epi->out_map < 0 || epi->out_map > 1 || epi->prologue < 0 || epi->prologue > 1) return HIDET_ERR_INVALID_ARG;
   if (conv && epi->out_map != HIDET_MAP_PLAIN) return HIDET_ERR_INVALID_ARG;
   const size_t es = (size_t)elem_size(dtype);
   if (epi->bias_axis != HIDET_BIAS_NONE && !aligned(epi->bias, es)) return HIDET_ERR_ALIGNMENT;
@@ -129,6 +129,7 @@ void fill_epilogue(GemmParams& p, const hidet_epilogue_t* epi) {
   p.ldr = 0;
   p.strideR = 0;
   p.relu = 0;
+  p.relu_a = p.relu_b = 0;
   p.out_map = 0;
   p.map_seq = p.map_d = p.map_heads = 1;
   p.d_seq = p.d_hd = make_fastdiv(1);
@@ -140,6 +141,7 @@ void fill_epilogue(GemmParams& p, const hidet_epilogue_t* epi) {
     p.ldr = epi->ld_residual;
     p.strideR = epi->batch_stride_residual;
     p.relu = epi->act == HIDET_ACT_RELU;
+    p.relu_a = epi->prologue == HIDET_PROLOGUE_RELU;  // the activation operand of a GEMM (make_conv_problem moves it to x)
   }
 }
 
@@ -276,6 +278,8 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
   p.ldc = 0;
   p.strideA = p.strideB = p.strideC = 0;
   fill_epilogue(p, epi);
+  p.relu_b = p.relu_a;  // the activation operand of the convolution is x, the B operand of the implicit GEMM
+  p.relu_a = 0;
   p.ldr = 0;
   p.strideR = 0;
   p.g = ConvGeom{(int)IC, (int)H, (int)W, (int)KH, (int)KW, (int)sh, (int)sw, (int)ph, (int)pw, (int)OH, (int)OW,
@@ -301,7 +305,9 @@ LaunchFn find_launcher(const Problem& pr, int config) {
   // general-schedule kernel (the element-mode variant, which is as fast as vector mode on aligned operands).
   // repacked weights: the K axis is (kh, kw, ic) and a K tile must lie within one filter tap
   if (pr.packed) return pr.p.g.IC % kConfigs[config].bk == 0 ? registry().fn[config][pr.dtype][kConvTapVariant] : nullptr;
-  const int elem = (pr.p.out_map != 0 && kConfigs[config].sched == 1) ? 1 : pr.elem_mode;
+  // The ring schedule is also built without the input prologue (its direct loads bypass the registers): such a
+  // problem takes the through-registers form likewise.
+  const int elem = ((pr.p.out_map != 0 || pr.p.relu_a != 0 || pr.p.relu_b != 0) && kConfigs[config].sched == 1) ? 1 : pr.elem_mode;
   const int variant = pr.op == 1 ? conv_variant(elem) : gemm_variant(pr.transA, pr.transB, elem);
   // fp32 output from 16-bit inputs: the kernels that the K-parallel form uses for its partial sums are ordinary
   // kernels with an fp32 output type
@@ -313,7 +319,8 @@ LaunchFn find_partial_launcher(const Problem& pr, int config) {
   if (config < 0 || config >= kNumConfigs) return nullptr;
   if (pr.packed)
     return pr.p.g.IC % kConfigs[config].bk == 0 ? registry().fn[config][pr.dtype][kConvTapVariant + 1] : nullptr;
-  const int variant = pr.op == 1 ? conv_variant(pr.elem_mode) : gemm_variant(pr.transA, pr.transB, pr.elem_mode);
+  const int elem = ((pr.p.relu_a != 0 || pr.p.relu_b != 0) && kConfigs[config].sched == 1) ? 1 : pr.elem_mode;  // as in find_launcher
+  const int variant = pr.op == 1 ? conv_variant(elem) : gemm_variant(pr.transA, pr.transB, elem);
   return registry().fn[config][pr.dtype][kPartialVariants + variant];
 }
 
@@ -350,7 +357,7 @@ int default_config(const Problem& pr, int slices = 1) {
     // the ring schedule runs GEMMs only: by direct-to-LDS loads when the operands are 16-byte aligned, with its
     // stages staged through registers when they are not
     const bool ring_any = r.sched == 1 && pr.op == 0 && pr.p.out_map == 0;
-    const bool ring = ring_any && pr.elem_mode == 0;
+    const bool ring = ring_any && pr.elem_mode == 0 && pr.p.relu_a == 0 && pr.p.relu_b == 0;
     // A ring tile keeps one workgroup per compute unit busy on its own (from four stages of K on).  With 129..191
     // of them the tile of half the size would need a second, mostly empty round of workgroups, so the larger one is
     // still the better choice; from 128 down the smaller tile fits into one round and wins.
@@ -425,7 +432,7 @@ std::string problem_key(const Problem& pr, bool with_workspace = false) {
   char buf[256];
   const GemmParams& p = pr.p;
   const int epi_kind = p.bias_axis | (p.residual ? 4 : 0) | (p.relu ? 8 : 0) | (p.alpha != 1.0f ? 16 : 0) |
-                       (p.out_map ? 32 : 0) | (pr.wide_out ? 64 : 0);
+                       (p.out_map ? 32 : 0) | (pr.wide_out ? 64 : 0) | ((p.relu_a || p.relu_b) ? 128 : 0);
   if (pr.op == 0)
     std::snprintf(buf, sizeof(buf), "gemm:t%d:%d%d:b%lld:%dx%dx%d:e%d:m%d", pr.dtype, pr.transA, pr.transB, pr.batch, p.M,
                   p.N, p.K, epi_kind, pr.elem_mode);
@@ -627,6 +634,9 @@ hidet_status_t make_conv_call(ConvCall& cc, int in, int out, long long Nb, long 
     }
     cc.pointwise = make_gemm_problem(cc.gemm, in, out, 0, 0, Nb, OC, H * W, IC, w, IC, 0, x, H * W, IC * H * W, y, H * W,
                                      OC * H * W, ep) == HIDET_OK;
+    // the activation operand is x here too: the B operand of this GEMM
+    cc.gemm.p.relu_b = cc.gemm.p.relu_a;
+    cc.gemm.p.relu_a = 0;
   }
   return HIDET_OK;
 }

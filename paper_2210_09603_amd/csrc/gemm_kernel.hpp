@@ -100,8 +100,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
     }
   };
   auto commit = [&](unsigned char* stage) {  // registers -> LDS
-    opa.store(ra, tid, stage);
-    opb.store(rb, tid, stage + Cfg::A_BYTES);
+    opa.store(ra, tid, stage, p.relu_a != 0);
+    opb.store(rb, tid, stage + Cfg::A_BYTES, p.relu_b != 0);
   };
   typename OpA::Frag fa[2][G][FM];
   typename OpB::Frag fb[2][G][FN];
@@ -385,8 +385,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
     opa.load_edge(ra, tid, S * BK, p.g);
     opb.load_edge(rb, tid, S * BK, p.g);
     __syncthreads();
-    opa.store(ra, tid, smem);
-    opb.store(rb, tid, smem + Cfg::A_BYTES);
+    opa.store(ra, tid, smem, p.relu_a != 0);
+    opb.store(rb, tid, smem + Cfg::A_BYTES, p.relu_b != 0);
     __syncthreads();
     load_frags(smem);
     mfmas();
@@ -478,8 +478,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong_regs(const GemmP
   };
   auto deposit = [&](int s) {  // registers -> ring slot s % 4
     unsigned char* slot = smem + (s & 3) * Cfg::STAGE_BYTES;
-    opa.store(ra, tid, slot);
-    opb.store(rb, tid, slot + Cfg::A_BYTES);
+    opa.store(ra, tid, slot, p.relu_a != 0);
+    opb.store(rb, tid, slot + Cfg::A_BYTES, p.relu_b != 0);
   };
 
   const int S = bc.k_len / BK;  // full stages
@@ -513,8 +513,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong_regs(const GemmP
     opa.load_edge(ra, tid, S * BK, p.g);
     opb.load_edge(rb, tid, S * BK, p.g);
     __syncthreads();
-    opa.store(ra, tid, smem);
-    opb.store(rb, tid, smem + Cfg::A_BYTES);
+    opa.store(ra, tid, smem, p.relu_a != 0);
+    opb.store(rb, tid, smem + Cfg::A_BYTES, p.relu_b != 0);
     __syncthreads();
     load_frags(smem);
     mfmas();

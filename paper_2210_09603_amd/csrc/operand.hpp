@@ -438,12 +438,27 @@ struct Operand {
   }
 
   // ---- registers -> LDS ---------------------------------------------------------------------
-  __device__ __forceinline__ void store(const u32x4 (&regs)[NL], int tid, unsigned char* tile) const {
+  // `relu`: the fused input prologue -- every element passes through f(v) = (v < 0 ? 0 : v) on its way into LDS.
+  // A negative value of any of the three types has its sign bit set, i.e. is negative as a signed integer of its
+  // width, and a non-negative one is its own integer image: a signed integer max with 0 is that f, two elements per
+  // instruction for the 16-bit types.
+  __device__ __forceinline__ void store(const u32x4 (&regs)[NL], int tid, unsigned char* tile, bool relu = false) const {
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
       const tmap::Task t = LoadMap::task(tid, q);
       u32x4 v = regs[q];
       if constexpr (GATHER) v = finish_window(q, v);
+      if (relu) {
+        if constexpr (IS_F32) {
+          typedef int i32x4 __attribute__((ext_vector_type(4)));
+          const i32x4 z = {0, 0, 0, 0};
+          v = __builtin_bit_cast(u32x4, __builtin_elementwise_max(__builtin_bit_cast(i32x4, v), z));
+        } else {
+          typedef short i16x8 __attribute__((ext_vector_type(8)));
+          const i16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+          v = __builtin_bit_cast(u32x4, __builtin_elementwise_max(__builtin_bit_cast(i16x8, v), z));
+        }
+      }
       if constexpr (!IS_F32) {
         const int swz = (LAYOUT == L_KC) ? swz_kc<CPR, MI>(t.i) : swz_mc<CPR, MI>(t.i);
         *reinterpret_cast<u32x4*>(tile + (t.i * CPR + (t.j ^ swz)) * 16) = v;

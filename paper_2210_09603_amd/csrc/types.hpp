@@ -85,6 +85,7 @@ struct GemmParams {
   int total_blocks;
   int k_slices;     // > 1: parallel reduction on K -- workgroup z of a tile works on K range [z*k_slice_len, ...)
   int k_slice_len;  // and writes raw fp32 partial sums to slice z of the workspace (C points at the workspace)
+  int relu_a, relu_b;   // fused input prologue: the operand's elements pass through ReLU on their way into LDS
   int out_map;          // MAP_PLAIN kernels: 0 row-major [M][ldc], 1 head split (see row_offset / col_offset)
   int map_seq, map_d;   // head split: rows per sequence, columns per head
   int map_heads;        // head split: N / map_d

@@ -114,9 +114,9 @@ def test_gemm_argument_validation_happens_before_any_launch():
     e.out_map = 2
     assert _gemm(L, epi=ctypes.byref(e)) == INVALID
     e.out_map = hb.HIDET_MAP_HEAD_SPLIT
-    e.reserved = 1
+    e.prologue = 2
     assert _gemm(L, epi=ctypes.byref(e)) == INVALID
-    e.reserved = 0
+    e.prologue = 0
     f16 = hb.HIDET_F16
     assert L.hidet_batched_gemm(f16, f16, 0, 0, 2, 8, 8, 8, 0x1000, 8, 64, 0x2000, 8, 64, 0x3000, 8, 64, ctypes.byref(e),
                                 None) == UNSUPPORTED
