@@ -448,6 +448,29 @@ def studies(torch, hb, wl, steps=100):
                               "untuned_call_us": round(untuned, 2),
                               "TFLOPs_best": round(flops / min(gather[0], gemm_form) * 1e-6, 2)})
     out["pointwise_conv_forms_f16"] = pointwise
+
+    # 3x3 convolutions: the (ic, kh, kw) K order over OIHW weights against the tap-major order over repacked weights
+    # (one filter tap per K tile); both tuned over tiles and K-slice counts, HIP-graph replays
+    packed = []
+    for nb in (1, 8, 64):
+        for IC, HW, OC, s_ in ((64, 56, 64, 1), (128, 28, 128, 1), (256, 14, 256, 1), (512, 7, 512, 1), (256, 28, 256, 2)):
+            c = wl.conv_case(6600 + nb + HW + s_, nb, IC, HW, HW, OC, 3, 3, s_, 1, "f16")
+            x, w, b = dev(c["x"]), dev(c["w"]), dev(c["bias"])
+            y = torch.empty((nb, OC, c["OH"], c["OW"]), dtype=torch.float16, device="cuda")
+            epi = hb.make_epilogue(bias=b, bias_axis=hb.HIDET_BIAS_PER_ROW, relu=True)
+            sp = dict(stride=(s_, s_), pad=(1, 1))
+            wp = hb.hidet_conv2d_pack_weights(w)
+            c0, s0, _ = hb.hidet_tune_conv2d_splitk(x, w, y, ws, epilogue=epi, iters=20, **sp)
+            t0 = graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm_splitk(x, w, y, ws, k_slices=s0, epilogue=epi, config=c0, **sp))
+            c1, s1, _ = hb.hidet_tune_conv2d_packed(x, wp, y, ws, epilogue=epi, iters=20, **sp)
+            t1 = graph_time(torch, lambda: hb.hidet_conv2d_implicit_gemm_packed(x, wp, y, epilogue=epi, config=c1, k_slices=s1,
+                                                                                workspace=ws, **sp))
+            flops = 2.0 * nb * OC * c["OH"] * c["OW"] * IC * 9
+            packed.append({"layer": "%dx%d %d->%d k3 s%d" % (HW, HW, IC, OC, s_), "batch": nb,
+                           "oihw_us": round(t0, 2), "oihw_tile": tile(c0), "oihw_k_slices": s0,
+                           "packed_us": round(t1, 2), "packed_tile": tile(c1), "packed_k_slices": s1,
+                           "TFLOPs_best": round(flops / min(t0, t1) * 1e-6, 2)})
+    out["conv3x3_weight_orders_f16"] = packed
     return out
 
 

@@ -302,7 +302,7 @@ hidet_status_t make_conv_problem(Problem& pr, int in, int out, long long Nb, lon
 LaunchFn find_launcher(const Problem& pr, int config) {
   if (config < 0 || config >= kNumConfigs) return nullptr;
   // The ring schedule is built without the run-time output map; a head-split problem takes the same tile's
-  // general-schedule kernel (the element-mode variant, which is as fast as vector mode on aligned operands).
+  // element-mode variant, whose launcher then picks the through-registers form of the schedule.
   // repacked weights: the K axis is (kh, kw, ic) and a K tile must lie within one filter tap
   if (pr.packed) return pr.p.g.IC % kConfigs[config].bk == 0 ? registry().fn[config][pr.dtype][kConvTapVariant] : nullptr;
   // The ring schedule is also built without the input prologue (its direct loads bypass the registers): such a
@@ -354,10 +354,10 @@ int default_config(const Problem& pr, int slices = 1) {
     if (r.sched == 3 && (pr.p.K < r.bk || throughput)) continue;
     const long long blocks =
         sat_mul(((M + r.bm - 1) / r.bm) * ((N + r.bn - 1) / r.bn), pr.batch * (slices > 1 ? slices : 1));
-    // the ring schedule runs GEMMs only: by direct-to-LDS loads when the operands are 16-byte aligned, with its
-    // stages staged through registers when they are not
+    // the ring schedule runs GEMMs only: by direct-to-LDS loads (at any element alignment), with its stages
+    // staged through registers when an input prologue has to touch the values
     const bool ring_any = r.sched == 1 && pr.op == 0 && pr.p.out_map == 0;
-    const bool ring = ring_any && pr.elem_mode == 0 && pr.p.relu_a == 0 && pr.p.relu_b == 0;
+    const bool ring = ring_any && pr.p.relu_a == 0 && pr.p.relu_b == 0;
     // A ring tile keeps one workgroup per compute unit busy on its own (from four stages of K on).  With 129..191
     // of them the tile of half the size would need a second, mostly empty round of workgroups, so the larger one is
     // still the better choice; from 128 down the smaller tile fits into one round and wins.

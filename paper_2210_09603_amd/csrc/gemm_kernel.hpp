@@ -271,6 +271,12 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
 // The second wave group enters the loop one barrier late and leaves it one barrier early.
 // A last partial stage (K not a multiple of BK) is staged through registers with zero fill after the
 // ring has drained.
+// Operands whose rows are only element aligned (odd leading dimensions, offset pointers -- the sizes on
+// which input-centric schedule spaces have no schedule, Section 3.3) run the same schedule: the direct
+// loads take any element-aligned address.  A direct load cannot be predicated, so there the LAST stage,
+// whole or partial, always goes through registers: no 16-byte chunk of a direct load then touches the
+// last row of a row-major operand, where reading past the last column would leave the allocation
+// (on every other row it reads the beginning of the next one, into columns that are never stored).
 // ---------------------------------------------------------------------------------------------
 // SLOTS = 2 is the same kernel for a K range of at most two stages: nothing is ever requested into a slot that was
 // used before, two slots of LDS are enough, and two such workgroups fit on a compute unit where the registers allow
@@ -281,10 +287,12 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
   using Acc = typename AccT<Cfg::MI>::type;
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, MI = Cfg::MI, NT = Cfg::NT;
   constexpr int FM = Cfg::FM, FN = Cfg::FN, KS = Cfg::KS;
-  static_assert(Cfg::NWAVES == 8 && !Cfg::IS_F32 && Cfg::MODE_A == LD_VEC && Cfg::MODE_B == LD_VEC && Cfg::STAGES == 4,
-                "ping-pong schedule: 8 waves, 16-bit vector mode, 4 LDS stages");
-  using OpA = Operand<T, BM, BK, Cfg::LA, LD_VEC, NT, MI>;
-  using OpB = Operand<T, BN, BK, Cfg::LB, LD_VEC, NT, MI>;
+  static_assert(Cfg::NWAVES == 8 && !Cfg::IS_F32 && Cfg::MODE_A == Cfg::MODE_B &&
+                    (Cfg::MODE_A == LD_VEC || Cfg::MODE_A == LD_ELEM) && Cfg::STAGES == 4,
+                "ping-pong schedule: 8 waves, 16-bit types, plain operands, 4 LDS stages");
+  constexpr bool ELEM = Cfg::MODE_A == LD_ELEM;  // rows only element aligned
+  using OpA = Operand<T, BM, BK, Cfg::LA, Cfg::MODE_A, NT, MI>;
+  using OpB = Operand<T, BN, BK, Cfg::LB, Cfg::MODE_B, NT, MI>;
   constexpr int LOADS = OpA::NL + OpB::NL;  // direct loads per thread per stage
 
   static_assert(SLOTS == 4 || SLOTS == 2, "ring of four stages, or two stages without reuse");
@@ -355,10 +363,11 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
       __builtin_amdgcn_s_waitcnt(0x0070);
   };
 
-  const int S = bc.k_len / BK;  // full stages
+  // stages loaded directly: the full ones; all but the last one for element-aligned operands
+  const int S = ELEM ? (bc.k_len > 0 ? (bc.k_len - 1) / BK : 0) : bc.k_len / BK;
   if (S > 0) {
-    opa.init_direct(tid);
-    opb.init_direct(tid);
+    opa.init_direct(tid, ELEM);
+    opb.init_direct(tid, ELEM);
     const int pre = S < 3 ? S : 3;
     for (int s = 0; s < pre; ++s) request(s);
     wait_stage(pre - 1);
@@ -378,7 +387,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
     }
     if (grp == 0) phase_barrier();
   }
-  if (S * BK < bc.k_len) {  // the partial last stage, through registers with zero fill
+  if (S * BK < bc.k_len) {  // the last stage (partial, or any for element-aligned operands), through registers with zero fill
     u32x4 ra[OpA::NL], rb[OpB::NL];
     opa.init(tid, p.g);
     opb.init(tid, p.g);
@@ -397,9 +406,9 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel_pingpong(const GemmParams
 }
 
 // ---------------------------------------------------------------------------------------------
-// The large-tile schedule for operands whose rows are only element aligned (odd leading dimensions,
-// offset pointers -- the sizes on which input-centric schedule spaces have no schedule, Section 3.3).
-// Direct global -> LDS loads need aligned addresses, so here a stage travels through registers: it is
+// The large-tile schedule with its stages staged through registers, for what a direct global -> LDS load
+// cannot do: an input prologue applied to the operand as it is loaded, and the head-split output map
+// (compiled out of the kernel above).  A stage is
 // requested (16-byte loads at element alignment) during the memory phase of one iteration, written
 // into its ring slot during the memory phase of the next, and multiplied one iteration after that.
 // Phases, barriers and the half-stage offset between the two wavefronts of a SIMD are those of

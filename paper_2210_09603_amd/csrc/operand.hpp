@@ -348,8 +348,12 @@ struct Operand {
   // fetches the logical chunk that belongs at that position.  The instruction is issued through
   // inline assembly and tracked by hand with s_waitcnt vmcnt(n): the schedule that uses it keeps
   // several stages in flight and waits for the oldest only.
+  // `in_place` (element-aligned operands): a chunk that sticks out past the last column of an M/N-contiguous
+  // operand is read where it lies -- what follows the row's end is the next row, and the columns it fills are never
+  // stored -- instead of being moved back to end at the edge, which is only right when whole chunks stick out.
+  // The caller keeps such loads away from the operand's last row.
   int doff[NL];
-  __device__ __forceinline__ void init_direct(int tid) {
+  __device__ __forceinline__ void init_direct(int tid, bool in_place = false) {
     static_assert(std::is_same<LoadMap, LoadMapRowMajor<SROWS, CPR, NT>>::value, "stored positions in row-major order");
 #pragma unroll
     for (int q = 0; q < NL; ++q) {
@@ -362,7 +366,8 @@ struct Operand {
         const int r = row < rows_left ? row : rows_left - 1;
         doff[q] = r * (int)ld + lc * VEC;
       } else {
-        const int c = lc * VEC + VEC <= rows_left ? lc * VEC : rows_left - VEC;
+        int c = lc * VEC + VEC <= rows_left ? lc * VEC : rows_left - VEC;
+        if (in_place) c = lc * VEC < rows_left ? lc * VEC : 0;
         doff[q] = row * (int)ld + c;
       }
     }

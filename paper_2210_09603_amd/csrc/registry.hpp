@@ -31,9 +31,12 @@ constexpr int kConvTapVariant = 20;   // convolution over the tap-major K order 
 
 template <class Cfg>
 hipError_t launch_kernel(const GemmParams& p, hipStream_t stream) {
-  if constexpr (Cfg::SCHED == SCHED_PINGPONG && Cfg::MODE_A == LD_ELEM)
-    hipLaunchKernelGGL(gemm_kernel_pingpong_regs<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
-  else if constexpr (Cfg::SCHED == SCHED_PINGPONG) {
+  // the element-mode variant of a ring tile also serves what the direct loads cannot do (input prologue, head-split
+  // output map), with its stages staged through registers
+  if (Cfg::SCHED == SCHED_PINGPONG && Cfg::MODE_A == LD_ELEM && (p.out_map != 0 || p.relu_a != 0 || p.relu_b != 0)) {
+    if constexpr (Cfg::SCHED == SCHED_PINGPONG && Cfg::MODE_A == LD_ELEM)
+      hipLaunchKernelGGL(gemm_kernel_pingpong_regs<Cfg>, dim3((unsigned)p.total_blocks), dim3(Cfg::NT), 0, stream, p);
+  } else if constexpr (Cfg::SCHED == SCHED_PINGPONG) {
     // a K range of at most two stages never reuses a ring slot: the two-slot form leaves LDS for a second workgroup
     const int k_len = p.k_slices > 1 ? p.k_slice_len : p.K;
     if (k_len <= 2 * Cfg::BK)

@@ -116,11 +116,13 @@ def test_every_config_on_an_odd_shape(dtype):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_ring_schedules_every_stage_count(dtype):
-    """The ring schedules (direct global -> LDS loads on aligned operands, stages through registers on element-aligned
-    ones) fill and drain a ring of four stages: K values that give 0, 1, 2, 3, 4, 5 and 9 full stages, each with
-    and without a partial last stage, on every ring configuration."""
+    """The ring schedules (direct global -> LDS loads, on aligned and on element-aligned operands) fill and drain a
+    ring of four stages: K values that give 0, 1, 2, 3, 4, 5 and 9 full stages, each with and without a partial last
+    stage, on every ring configuration.  Element-aligned rows come from an odd K (row-major A, transposed B) and,
+    with K a whole number of stages, from odd M and N (row-major B, transposed A, the output)."""
     ring = [i for i in applicable_configs(dtype) if hb.hidet_config_info(i)["schedule"] == 1]
     assert ring
+    ran_trans_a = 0
     for cfg in ring:
         bk = hb.hidet_config_info(cfg)["block_k"]
         for stages in (0, 1, 2, 3, 4, 5, 9):
@@ -128,13 +130,51 @@ def test_ring_schedules_every_stage_count(dtype):
                 K = stages * bk + tail
                 if K == 0:
                     continue
-                aligned = tail % 8 == 0
-                M, N = (264, 520) if aligned else (263, 517)  # odd sizes: element-aligned rows
-                for tB in (False, True):
-                    c = wl.gemm_case(7450 + cfg, M, N, K, dtype, transB=tB, bias="col")
-                    err, _, ref = run_gemm_case(c, config=cfg, relu=True)
-                    assert within_bound(err, ref, dtype), (cfg, stages, tail, tB, err)
+                for odd in ((False, True) if tail % 8 == 0 else (True,)):
+                    M, N = (263, 517) if odd else (264, 520)  # odd sizes: element-aligned rows
+                    for tA, tB in ((False, False), (False, True), (True, False), (True, True)):
+                        if tA and (stages not in (1, 4) or tail == 8):
+                            continue  # the transposed-A forms on a few stage counts only
+                        c = wl.gemm_case(7450 + cfg, M, N, K, dtype, transA=tA, transB=tB, bias="col")
+                        try:
+                            err, _, ref = run_gemm_case(c, config=cfg, relu=True)
+                        except hb.HidetError as e:
+                            assert tA and e.status == 4, (cfg, stages, tail, tA, tB, e)  # tile built without transposed A
+                            continue
+                        ran_trans_a += int(tA)
+                        assert within_bound(err, ref, dtype), (cfg, stages, tail, odd, tA, tB, err)
+    assert ran_trans_a > 0
     _say("ring configurations %s: all stage counts pass (%s)" % (ring, dtype))
+
+
+def test_ring_schedule_on_offset_pointers_and_padded_rows():
+    """Element alignment from the pointers alone: operands and output that start one element into their buffers, with
+    leading dimensions larger than the rows, on the 256x256 ring tile; K spans whole stages and a tail."""
+    cfg = next(i for i in applicable_configs("f16")
+               if hb.hidet_config_info(i)["schedule"] == 1 and hb.hidet_config_info(i)["block_m"] == 256
+               and hb.hidet_config_info(i)["block_n"] == 256 and hb.hidet_config_info(i)["mfma"] == 16)
+    for M, N, K in ((300, 520, 128), (257, 263, 167), (512, 256, 96)):
+        c = wl.gemm_case(7470 + K, M, N, K, "f16", bias="col", lda_pad=16, ldb_pad=24)
+        bufA = torch.zeros(M * c["lda"] + 1, dtype=torch.float16, device="cuda")
+        bufB = torch.zeros(K * c["ldb"] + 1, dtype=torch.float16, device="cuda")
+        bufC = torch.full((M * (N + 9) + 1,), float("nan"), dtype=torch.float16, device="cuda")
+        A = bufA[1:].view(M, c["lda"])
+        B = bufB[1:].view(K, c["ldb"])
+        A.copy_(to_gpu(c["A"], "f16"))
+        B.copy_(to_gpu(c["B"], "f16"))
+        C = bufC[1:].view(M, N + 9)[:, :N]
+        bias = to_gpu(c["bias"], "f16")
+        hb.hidet_gemm(A[:, :K], B[:, :N], C, epilogue=hb.make_epilogue(bias=bias, bias_axis=hb.HIDET_BIAS_PER_COL, relu=True),
+                      config=cfg)
+        torch.cuda.synchronize()
+        A64, B64 = wl.widen(c["A"], "f16")[:, :K], wl.widen(c["B"], "f16")[:, :N]
+        ref = oracle.gemm(A64, B64, bias=wl.widen(c["bias"], "f16"), bias_axis=oracle.BIAS_PER_COL, relu=True)
+        got = to_f64(C)
+        err = oracle.rel_frobenius(got, ref)
+        assert within_bound(err, ref, "f16"), (M, N, K, err)
+        # what lies between the rows of the output, and before it, is untouched
+        whole = bufC[1:].view(M, N + 9)
+        assert torch.isnan(whole[:, N:]).all() and torch.isnan(bufC[0])
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
