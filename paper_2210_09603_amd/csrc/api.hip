@@ -220,6 +220,8 @@ hidet_status_t make_gemm_problem(Problem& pr, int in, int out, int transA, int t
     vs = contiguous4 && aligned(C, va) && (!p.residual || aligned(p.residual, va));
   }
   p.vec_store = vs ? 2 : (contiguous4 ? 1 : 0);
+  // rows at least 4 KB apart: write the output through the L2 (see store_group)
+  if (vs && p.out_map == 0 && elem_size(out) == 2 && p.ldc * 2 >= 4096) p.vec_store = 3;
   p.out_inner = 1;
   p.out_outer = 0;
   std::memset(&p.g, 0, sizeof(p.g));

@@ -256,7 +256,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// The kernel, large-tile schedule: 8 waves (2 per SIMD), vector mode only.
+// The kernel, large-tile schedule: 8 waves (2 per SIMD), plain 16-bit operands.
 //
 // K is consumed in stages of BK; LDS holds a ring of 4 stages.  Stage s+3 is requested with direct
 // global -> LDS loads while stage s is being multiplied, so a load has two full stages to land.

@@ -342,7 +342,7 @@ struct Operand {
     }
   }
 
-  // Direct global -> LDS loads (vector mode, 16-bit types).  Lane l of a wave writes its 16 bytes at
+  // Direct global -> LDS loads (16-bit types, plain operands at any element alignment).  Lane l of a wave writes its 16 bytes at
   // LDS[base + 16*l], so the LDS side of the cooperative load is fixed -- thread t's q-th load fills
   // stored position q*NT + t of the tile -- and the swizzle moves to the global side: the thread
   // fetches the logical chunk that belongs at that position.  The instruction is issued through

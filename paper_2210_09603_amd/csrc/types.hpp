@@ -80,7 +80,8 @@ struct GemmParams {
   int bias_axis;  // 0 none, 1 per column, 2 per row
   int relu;
   int vec_store;  // groups of 4 consecutive output columns are contiguous in memory and may use one access:
-                  // 0 no, 1 yes at element alignment, 2 yes and every group is aligned to 4 elements
+                  // 0 no, 1 yes at element alignment, 2 yes and every group is aligned to 4 elements,
+                  // 3 as 2 and the groups are written through the L2 (row-major 16-bit output with rows >= 4 KB apart)
   int tiles_m, tiles_n, group;
   int total_blocks;
   int k_slices;     // > 1: parallel reduction on K -- workgroup z of a tile works on K range [z*k_slice_len, ...)
