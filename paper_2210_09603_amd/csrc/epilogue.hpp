@@ -62,10 +62,10 @@ __device__ __forceinline__ int group_valid(const GemmParams& p, int n) {
 // Four 16-bit outputs as one 8-byte store.  The L2s are private to a die and write back what is dirty when the kernel
 // ends; a kernel that ends by writing 32 MB spends 4-5 us there after its last instruction.  `through`: the store
 // writes through the L2 (device scope), so nothing is left for that write-back -- measured 2 % (4096^3) to 9 %
-// (4096 x 4096 x 256) faster.  The host asks for it only when the output's rows lie at least 4 KB apart: with
-// short rows (the 1 KB rows of 512 x 512 attention scores) the immediate write of every 128-byte piece scatters
-// over DRAM pages that several workgroups fill, and a 100 MB output that misses the Infinity Cache took 28 %
-// longer; there the store is a streaming one and the L2 gathers the lines first.
+// (4096 x 4096 x 256) faster.  The host asks for it only when the output's rows lie at least 4 KB apart, which is
+// where it was measured to gain with the output in the Infinity Cache and out of it (2048 and 4096 columns).  With
+// the 1 KB rows of 512 x 512 attention scores a 100 MB output that misses the Infinity Cache took 28 % longer when
+// written through (also with tiles that span whole rows); there the store is a streaming one.
 template <typename TO>
 __device__ __forceinline__ void store_group(TO* dst, const TO (&o)[4], bool through) {
   static_assert(sizeof(TO) == 2, "8-byte group");
