@@ -290,11 +290,21 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False, cold
                  "flops": 2.0 * 256 * c["OH"] * c["OW"] * 256 * 9}
     for _ in range(warmup):
         step()
+    # The K timed steps are captured into one HIP graph and replayed once between the two events: kernels of a few
+    # tens of microseconds are otherwise launched more slowly from Python than they run.  (The library only launches
+    # kernels, so a call may be captured; the graph is replayed once untimed first.)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(steps):
+                step()
+    g.replay()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
-    for _ in range(steps):
-        step()
+    g.replay()
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
@@ -311,8 +321,6 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False, cold
         out.update(metric="TFLOP/s of one secondary kernel, 1 GPU", value=round(tf, 2), unit="TFLOP/s", dtype="f32")
         out["roofline"] = {"bound": "mfma", "achieved": round(tf, 2), "peak": 157.3, "unit": "TFLOP/s",
                            "frac": round(tf / 157.3, 4), "traffic": None}
-    # Kernels of a few microseconds are launched more slowly from Python than they run: the same call replayed from a
-    # HIP graph gives the device-side time per call.
     if graph_replay:
         out["config"]["us_per_call_graph_replay"] = round(graph_time(torch, step), 2)
     return out
