@@ -386,6 +386,12 @@ hidet_status_t hidet_probe_launch_floor(void* stream, int32_t iters, float* us_p
 const char* hidet_status_string(int32_t status);
 /* Library version string and the GPU architecture the kernels were compiled for ("gfx950"). */
 const char* hidet_version(void);
+/*
+ * Number of GEMM / convolution kernels the calling thread has launched through this library so far (a call launches
+ * one; two when K is sliced -- partial sums, then reduce + epilogue; two when an untuned large GEMM is cut into the
+ * tile rows that fill whole rounds of the compute units and the rest).  Measurement and test aid; never fails.
+ */
+int64_t hidet_kernel_launch_count(void);
 
 #ifdef __cplusplus
 }

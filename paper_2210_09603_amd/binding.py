@@ -58,6 +58,7 @@ EXPORTS = (
     "hidet_conv2d_implicit_gemm_cfg", "hidet_config_count", "hidet_config_info", "hidet_tune_gemm", "hidet_tune_conv2d",
     "hidet_tune_last_times", "hidet_tune_clear", "hidet_tune_save", "hidet_tune_load", "hidet_taskmap_count",
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
+    "hidet_kernel_launch_count",
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_probe_launch_floor", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
     "hidet_softmax_rows", "hidet_host_div", "hidet_conv2d_splitk_workspace_bytes", "hidet_static_scratch_bytes",
@@ -122,6 +123,7 @@ def lib():
         L.hidet_status_string.argtypes = [_i32]
         L.hidet_status_string.restype = ctypes.c_char_p
         L.hidet_version.restype = ctypes.c_char_p
+        L.hidet_kernel_launch_count.restype = ctypes.c_int64
         _lib = L
     return _lib
 
@@ -516,3 +518,7 @@ def hidet_probe_mfma_peak(sample, mfma=16, stream=None):
 
 def hidet_version():
     return lib().hidet_version().decode()
+
+
+def hidet_kernel_launch_count():
+    return int(lib().hidet_kernel_launch_count())

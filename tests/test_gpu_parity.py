@@ -654,3 +654,38 @@ def test_mfma_ceiling_probe_reports_plausible_numbers():
     floor = hb.hidet_probe_launch_floor(500)
     _say("launch floor %.2f us" % floor)
     assert 0.5 < floor < 50.0
+
+
+# ------------------------------------------------------------------ tile quantisation: rows split for whole rounds
+@pytest.mark.parametrize("transA,bias", [(False, "row"), (False, "col"), (True, "row")])
+def test_untuned_large_gemm_is_cut_into_whole_rounds_and_the_rest(transA, bias):
+    """17 x 17 tiles of 256 x 256 are one round of the 256 compute units plus 33 tiles: an untuned call runs the
+    first 15 tile rows on the large tile and the remaining rows as a problem of its own (two launches), and the
+    result is that of the whole problem -- row bias, residual and a transposed A follow the cut."""
+    M = N = 4352
+    K = 160
+    hb.hidet_tune_clear()
+    c = wl.gemm_case(7700 + int(transA) + (1 if bias == "row" else 0) * 2, M, N, K, "f16", transA=transA, bias=bias, residual=True)
+    before = hb.hidet_kernel_launch_count()
+    err, got, ref = run_gemm_case(c, relu=True, alpha=0.5)
+    launches = hb.hidet_kernel_launch_count() - before
+    _say("4352^2 x %d tA%d bias %s: err %.3e, %d launches" % (K, transA, bias, err, launches))
+    assert err <= TOL["f16"]
+    assert launches == 2
+    # an explicit configuration is never cut
+    before = hb.hidet_kernel_launch_count()
+    cfg = next(i for i in applicable_configs("f16") if hb.hidet_config_info(i)["schedule"] == 1
+               and hb.hidet_config_info(i)["block_m"] == 256 and hb.hidet_config_info(i)["block_n"] == 256
+               and hb.hidet_config_info(i)["mfma"] == (32 if transA else 16))
+    err, _, _ = run_gemm_case(c, config=cfg, relu=True, alpha=0.5)
+    assert err <= TOL["f16"] and hb.hidet_kernel_launch_count() - before == 1
+
+
+def test_kernel_launch_count_of_plain_and_k_sliced_calls():
+    c = wl.gemm_case(7710, 96, 200, 1024, "f16", bias="col")
+    before = hb.hidet_kernel_launch_count()
+    run_gemm_case(c)
+    assert hb.hidet_kernel_launch_count() - before == 1
+    before = hb.hidet_kernel_launch_count()
+    run_gemm_case(c, k_slices=4, config=sliceable_configs("f16")[0])
+    assert hb.hidet_kernel_launch_count() - before == 2
