@@ -388,8 +388,8 @@ const char* hidet_status_string(int32_t status);
 const char* hidet_version(void);
 /*
  * Number of GEMM / convolution kernels the calling thread has launched through this library so far (a call launches
- * one; two when K is sliced -- partial sums, then reduce + epilogue; two when an untuned large GEMM is cut into the
- * tile rows that fill whole rounds of the compute units and the rest).  Measurement and test aid; never fails.
+ * one; two when K is sliced -- partial sums, then reduce + epilogue; two when a large GEMM for which the caller
+ * named no configuration is cut into the tile rows that fill whole rounds of the compute units and the rest).  Measurement and test aid; never fails.
  */
 int64_t hidet_kernel_launch_count(void);
 

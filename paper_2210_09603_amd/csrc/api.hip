@@ -498,26 +498,25 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
     }
     if (slices < 0) slices = 1;
     // (a remembered configuration that has no K-parallel form cannot serve an explicit slice count)
-    if (config < 0 || !find_launcher(pr, config) || (slices > 1 && !find_partial_launcher(pr, config))) {
+    if (config < 0 || !find_launcher(pr, config) || (slices > 1 && !find_partial_launcher(pr, config)))
       config = default_config(pr, slices);
-      // Untuned GEMM on the 256x256 ring tile whose tiles fill whole rounds of the 256 compute units plus a thin
-      // last round (at most a quarter full): the tile rows that make up the whole rounds run as they are, the remaining
-      // rows run as a problem of their own, for which the size-based choice takes a smaller tile that fills the
-      // device.  Two launches on the same stream, no partial sums: every output element is still computed by one
-      // workgroup over the whole of K.
-      const long long rows = config >= 0 ? split_rows_for_whole_rounds(pr, config, slices) : 0;
-      if (rows > 0) {
-        Problem head = pr, tail = pr;
-        head.p.M = (int)rows;
-        tail.p.M = p.M - (int)rows;
-        const long long es_in = elem_size(pr.dtype), es_out = pr.wide_out ? 4 : es_in;
-        tail.p.A = static_cast<const char*>(p.A) + (pr.transA ? rows : rows * p.lda) * es_in;
-        tail.p.C = static_cast<char*>(p.C) + rows * p.ldc * es_out;
-        if (p.residual) tail.p.residual = static_cast<const char*>(p.residual) + rows * p.ldr * es_out;
-        if (p.bias && p.bias_axis == 2) tail.p.bias = static_cast<const char*>(p.bias) + rows * es_out;
-        const hidet_status_t st = launch(head, config, sk, stream);
-        return st != HIDET_OK ? st : launch(tail, -1, sk, stream);
-      }
+    // A GEMM for which the caller named no configuration (size-based or remembered choice), on the 256x256 ring tile,
+    // whose tiles fill whole rounds of the 256 compute units plus a thin last round (at most a quarter full): the
+    // tile rows that make up the whole rounds run as they are, the remaining rows run as a problem of their own, for
+    // which the size-based choice takes a smaller tile that fills the device.  Two launches on the same stream, no
+    // partial sums: every output element is still computed by one workgroup over the whole of K.
+    const long long rows = config >= 0 ? split_rows_for_whole_rounds(pr, config, slices) : 0;
+    if (rows > 0) {
+      Problem head = pr, tail = pr;
+      head.p.M = (int)rows;
+      tail.p.M = p.M - (int)rows;
+      const long long es_in = elem_size(pr.dtype), es_out = pr.wide_out ? 4 : es_in;
+      tail.p.A = static_cast<const char*>(p.A) + (pr.transA ? rows : rows * p.lda) * es_in;
+      tail.p.C = static_cast<char*>(p.C) + rows * p.ldc * es_out;
+      if (p.residual) tail.p.residual = static_cast<const char*>(p.residual) + rows * p.ldr * es_out;
+      if (p.bias && p.bias_axis == 2) tail.p.bias = static_cast<const char*>(p.bias) + rows * es_out;
+      const hidet_status_t st = launch(head, config, sk, stream);
+      return st != HIDET_OK ? st : launch(tail, -1, sk, stream);
     }
   }
   if (slices < 0) slices = 1;

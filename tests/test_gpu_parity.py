@@ -7,7 +7,7 @@ import oracle
 from paper_2210_09603_amd import binding as hb
 from paper_2210_09603_amd import workloads as wl
 
-from helpers import (TOL, TORCH_DTYPE, applicable_configs, assert_elementwise, make_conv_workspace, make_workspace, run_conv_case, run_gemm_case, sliceable_configs,
+from helpers import (TOL, TORCH_DTYPE, applicable_configs, assert_elementwise, bias_axis_code, make_conv_workspace, make_workspace, run_conv_case, run_gemm_case, sliceable_configs,
                      to_f64, to_gpu, within_bound)
 
 pytestmark = pytest.mark.gpu
@@ -679,6 +679,17 @@ def test_untuned_large_gemm_is_cut_into_whole_rounds_and_the_rest(transA, bias):
                and hb.hidet_config_info(i)["mfma"] == (32 if transA else 16))
     err, _, _ = run_gemm_case(c, config=cfg, relu=True, alpha=0.5)
     assert err <= TOL["f16"] and hb.hidet_kernel_launch_count() - before == 1
+    # a remembered (tuned) configuration is cut like the size-based one when it is the large ring tile
+    A, B = to_gpu(c["A"], "f16"), to_gpu(c["B"], "f16")
+    Av = A[:, :M] if transA else A[:, :K]
+    epi = hb.make_epilogue(alpha=0.5, bias=to_gpu(c["bias"], "f16"), bias_axis=bias_axis_code(c["bias_axis"]),
+                           residual=to_gpu(c["residual"], "f16"), relu=True)
+    hb.hidet_tune_gemm(Av, B[:, :N], torch.empty((M, N), dtype=torch.float16, device="cuda"), transA=transA, epilogue=epi,
+                       iters=3)
+    before = hb.hidet_kernel_launch_count()
+    err, _, _ = run_gemm_case(c, relu=True, alpha=0.5)
+    assert err <= TOL["f16"] and hb.hidet_kernel_launch_count() - before in (1, 2)
+    hb.hidet_tune_clear()
 
 
 def test_kernel_launch_count_of_plain_and_k_sliced_calls():
