@@ -463,23 +463,34 @@ hipError_t reduce_dispatch(int dtype, const GemmParams& p, int batch, hipStream_
 
 thread_local long long g_kernel_launches = 0;  // GEMM / convolution kernels this thread has launched so far
 
-// Rows (a multiple of 256) that the 256x256 ring tile should take when the rest is better served by a smaller tile,
-// or 0.  With T tiles of 256x256, T / 256 whole rounds keep every compute unit busy; a thin last round leaves most
+// The part of a GEMM (rows or columns, a multiple of 256) that the 256x256 ring tile should take when the rest is
+// better served by a smaller tile; none if both extents are 0.  With T tiles of 256x256, T / 256 whole rounds keep every compute unit busy; a thin last round leaves most
 // of the device idle for 0.6 of a tile's time (measured: it runs at a higher clock than a full round).  At most 64
 // left-over tiles make at most 256 tiles of 128x128, one round that takes 0.3 to 0.45 of that time; more of them
 // would need the 128x256 tile (0.6: no gain) or a second round.  Measured, 4352^3: 196 -> 154 us; 7168^3: 643 -> 602 us.
-long long split_rows_for_whole_rounds(const Problem& pr, int config, int slices) {
+// (The cut is made along M or along N, whichever leaves fewer tiles over.)
+struct RoundCut {
+  long long rows = 0, cols = 0;  // at most one is non-zero: extent of the head along M or along N
+};
+RoundCut cut_for_whole_rounds(const Problem& pr, int config, int slices) {
+  RoundCut cut;
   const ConfigRow& r = kConfigs[config];
   const GemmParams& p = pr.p;
-  if (pr.op != 0 || pr.batch != 1 || slices > 1 || p.out_map != 0) return 0;
-  if (r.sched != 1 || r.bm != 256 || r.bn != 256) return 0;
+  if (pr.op != 0 || pr.batch != 1 || slices > 1 || p.out_map != 0) return cut;
+  if (r.sched != 1 || r.bm != 256 || r.bn != 256) return cut;
   const long long tm = (p.M + 255) / 256, tn = (p.N + 255) / 256, tiles = tm * tn;
   const long long whole = tiles / 256;
-  if (whole < 1 || tiles % 256 == 0) return 0;
-  const long long head_rows = whole * 256 / tn;  // tile rows that fit into the whole rounds
-  if (head_rows < 1 || head_rows >= tm) return 0;
-  if ((tm - head_rows) * tn > 64) return 0;      // the rest must fit one round of 128x128 tiles
-  return head_rows * 256;
+  if (whole < 1 || tiles % 256 == 0) return cut;
+  // tile rows (columns) that fit into the whole rounds, and the 256x256 tiles left over
+  const long long head_rows = whole * 256 / tn, head_cols = whole * 256 / tm;
+  const long long rest_rows = head_rows >= 1 && head_rows < tm ? (tm - head_rows) * tn : -1;
+  const long long rest_cols = head_cols >= 1 && head_cols < tn ? (tn - head_cols) * tm : -1;
+  const bool rows_ok = rest_rows >= 0 && rest_rows <= 64, cols_ok = rest_cols >= 0 && rest_cols <= 64;  // one round of 128x128 tiles
+  if (rows_ok && (!cols_ok || rest_rows <= rest_cols))
+    cut.rows = head_rows * 256;
+  else if (cols_ok)
+    cut.cols = head_cols * 256;
+  return cut;
 }
 
 hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStream_t stream) {
@@ -502,19 +513,30 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
       config = default_config(pr, slices);
     // A GEMM for which the caller named no configuration (size-based or remembered choice), on the 256x256 ring tile,
     // whose tiles fill whole rounds of the 256 compute units plus a thin last round (at most a quarter full): the
-    // tile rows that make up the whole rounds run as they are, the remaining rows run as a problem of their own, for
-    // which the size-based choice takes a smaller tile that fills the device.  Two launches on the same stream, no
+    // tile rows (or columns) that make up the whole rounds run as they are, the remaining ones run as a problem of their
+    // own, for which the size-based choice takes a smaller tile that fills the device.  Two launches on the same stream, no
     // partial sums: every output element is still computed by one workgroup over the whole of K.
-    const long long rows = config >= 0 ? split_rows_for_whole_rounds(pr, config, slices) : 0;
-    if (rows > 0) {
+    const RoundCut cut = config >= 0 ? cut_for_whole_rounds(pr, config, slices) : RoundCut();
+    if (cut.rows > 0 || cut.cols > 0) {
       Problem head = pr, tail = pr;
-      head.p.M = (int)rows;
-      tail.p.M = p.M - (int)rows;
       const long long es_in = elem_size(pr.dtype), es_out = pr.wide_out ? 4 : es_in;
-      tail.p.A = static_cast<const char*>(p.A) + (pr.transA ? rows : rows * p.lda) * es_in;
-      tail.p.C = static_cast<char*>(p.C) + rows * p.ldc * es_out;
-      if (p.residual) tail.p.residual = static_cast<const char*>(p.residual) + rows * p.ldr * es_out;
-      if (p.bias && p.bias_axis == 2) tail.p.bias = static_cast<const char*>(p.bias) + rows * es_out;
+      if (cut.rows > 0) {
+        const long long rows = cut.rows;
+        head.p.M = (int)rows;
+        tail.p.M = p.M - (int)rows;
+        tail.p.A = static_cast<const char*>(p.A) + (pr.transA ? rows : rows * p.lda) * es_in;
+        tail.p.C = static_cast<char*>(p.C) + rows * p.ldc * es_out;
+        if (p.residual) tail.p.residual = static_cast<const char*>(p.residual) + rows * p.ldr * es_out;
+        if (p.bias && p.bias_axis == 2) tail.p.bias = static_cast<const char*>(p.bias) + rows * es_out;
+      } else {
+        const long long cols = cut.cols;
+        head.p.N = (int)cols;
+        tail.p.N = p.N - (int)cols;
+        tail.p.B = static_cast<const char*>(p.B) + (pr.transB ? cols * p.ldb : cols) * es_in;
+        tail.p.C = static_cast<char*>(p.C) + cols * es_out;
+        if (p.residual) tail.p.residual = static_cast<const char*>(p.residual) + cols * es_out;
+        if (p.bias && p.bias_axis == 1) tail.p.bias = static_cast<const char*>(p.bias) + cols * es_out;
+      }
       const hidet_status_t st = launch(head, config, sk, stream);
       return st != HIDET_OK ? st : launch(tail, -1, sk, stream);
     }

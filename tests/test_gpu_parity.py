@@ -700,3 +700,16 @@ def test_kernel_launch_count_of_plain_and_k_sliced_calls():
     before = hb.hidet_kernel_launch_count()
     run_gemm_case(c, k_slices=4, config=sliceable_configs("f16")[0])
     assert hb.hidet_kernel_launch_count() - before == 2
+
+
+def test_wide_gemm_is_cut_by_columns_for_whole_rounds():
+    """8 x 37 tiles of 256 x 256: the whole round is 32 tile columns, the rest (5 x 8 tiles) runs on its own; column
+    bias, residual and a transposed B follow the cut."""
+    M, N, K = 2048, 9472, 160
+    hb.hidet_tune_clear()
+    for transB in (False, True):
+        c = wl.gemm_case(7720 + int(transB), M, N, K, "f16", transB=transB, bias="col", residual=True)
+        before = hb.hidet_kernel_launch_count()
+        err, _, _ = run_gemm_case(c, relu=True, alpha=0.5)
+        assert err <= TOL["f16"]
+        assert hb.hidet_kernel_launch_count() - before == 2, transB
