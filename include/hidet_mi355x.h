@@ -17,9 +17,10 @@
  *     accumulated in fp32.  The output is rounded once (nearest-even) to `out` after the epilogue.
  *   - Sizes are arbitrary: tiles that stick out of the problem are handled by predicated loads and
  *     stores (the hardware-centric schedule space of Section 4.3 does not depend on input sizes).
- *   - On any status other than HIDET_OK no output byte was written, and nothing has been launched unless the
- *     status is HIDET_ERR_LAUNCH from a K-parallel form (its first kernel, which writes the workspace only, may
- *     have run).  No C++ exception leaves the library; a failed host allocation is reported as HIDET_ERR_LAUNCH.
+ *   - On any status other than HIDET_OK nothing has been launched and no output byte was written, unless the
+ *     status is HIDET_ERR_LAUNCH (the HIP runtime refused a launch) from a call that launches two kernels: a
+ *     K-parallel form, whose first kernel writes the workspace only, or a large GEMM cut in two (see
+ *     hidet_kernel_launch_count), whose first kernel writes its rows or columns of C.  No C++ exception leaves the library; a failed host allocation is reported as HIDET_ERR_LAUNCH.
  *     M == 0, N == 0 or batch == 0 is an OK no-op; K == 0 writes C = epilogue(0).
  *   - Thread safety: entry points may be called from several host threads; the tuned-config cache
  *     is guarded by a mutex.

@@ -537,8 +537,12 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
         if (p.residual) tail.p.residual = static_cast<const char*>(p.residual) + cols * es_out;
         if (p.bias && p.bias_axis == 1) tail.p.bias = static_cast<const char*>(p.bias) + cols * es_out;
       }
-      const hidet_status_t st = launch(head, config, sk, stream);
-      return st != HIDET_OK ? st : launch(tail, -1, sk, stream);
+      // the rest's configuration is settled before anything is launched: a call that fails has written nothing
+      const int tail_config = default_config(tail, 1);
+      if (tail_config >= 0 && find_launcher(tail, tail_config) && find_launcher(head, config)) {
+        const hidet_status_t st = launch(head, config, sk, stream);
+        return st != HIDET_OK ? st : launch(tail, tail_config, sk, stream);
+      }
     }
   }
   if (slices < 0) slices = 1;
