@@ -316,6 +316,13 @@ def other_workload(torch, hb, wl, which, steps, warmup, graph_replay=False, cold
                         "frac": round(gbps / 8000.0, 4), "traffic": None}}
     if "flops" in extra:
         out["config"]["TFLOPs"] = round(extra["flops"] / (ms * 1e-3) / 1e12, 2)
+    if which in ("qkt", "sv", "softmax"):
+        # what plain read / write / copy kernels sustain on this machine on memory that no cache holds: the ceiling a
+        # memory-bound kernel can be held against (the 8 TB/s of the roofline is the datasheet's figure)
+        ring = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        out["config"]["streaming_kernel_GBps"] = {k: round(hb.hidet_probe_stream_bandwidth(ring, m), 1)
+                                                  for m, k in enumerate(("read", "write", "copy"))}
+        del ring
     if which == "gemm32":
         tf = extra["flops"] / (ms * 1e-3) / 1e12
         out.update(metric="TFLOP/s of one secondary kernel, 1 GPU", value=round(tf, 2), unit="TFLOP/s", dtype="f32")

@@ -383,6 +383,17 @@ int64_t hidet_probe_scratch_bytes(void);
  * are reported next to it.  Synchronises `stream`.  HIDET_ERR_INVALID_ARG for iters <= 0 or a NULL result.
  */
 hidet_status_t hidet_probe_launch_floor(void* stream, int32_t iters, float* us_per_launch);
+/*
+ * Streaming rate of a plain kernel (measurement aid): GB/s that a kernel which only reads (mode 0), only writes
+ * (mode 1) or copies (mode 2, bytes read + bytes written) sustains on memory that no cache holds -- the ceiling the
+ * memory-bound workloads are reported against beside the datasheet's 8 TB/s.  `buffer`: DEVICE memory of `bytes`
+ * bytes, 16-byte aligned, contents overwritten; it is walked in pieces of 128 MiB (48 launches), so 1 GiB or more
+ * keeps every piece out of the 256 MB Infinity Cache; at least 256 MiB.  Synchronises `stream`.
+ * HIDET_ERR_INVALID_ARG for a NULL pointer, an unknown mode or fewer than two pieces, HIDET_ERR_ALIGNMENT for a
+ * misaligned buffer.
+ */
+hidet_status_t hidet_probe_stream_bandwidth(void* buffer, int64_t bytes, int32_t mode, void* stream,
+                                            float* gbytes_per_s);
 
 const char* hidet_status_string(int32_t status);
 /* Library version string and the GPU architecture the kernels were compiled for ("gfx950"). */

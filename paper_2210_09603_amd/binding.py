@@ -58,7 +58,7 @@ EXPORTS = (
     "hidet_conv2d_implicit_gemm_cfg", "hidet_config_count", "hidet_config_info", "hidet_tune_gemm", "hidet_tune_conv2d",
     "hidet_tune_last_times", "hidet_tune_clear", "hidet_tune_save", "hidet_tune_load", "hidet_taskmap_count",
     "hidet_taskmap_info", "hidet_taskmap_tasks", "hidet_block_task", "hidet_status_string", "hidet_version",
-    "hidet_kernel_launch_count",
+    "hidet_kernel_launch_count", "hidet_probe_stream_bandwidth",
     "hidet_probe_mfma_peak", "hidet_probe_scratch_bytes", "hidet_probe_launch_floor", "hidet_splitk_workspace_bytes", "hidet_batched_gemm_splitk",
     "hidet_conv2d_implicit_gemm_splitk", "hidet_tune_gemm_splitk", "hidet_tune_conv2d_splitk", "hidet_reduce_rows",
     "hidet_softmax_rows", "hidet_host_div", "hidet_conv2d_splitk_workspace_bytes", "hidet_static_scratch_bytes",
@@ -120,6 +120,7 @@ def lib():
                                             ctypes.POINTER(ctypes.c_float)]
         L.hidet_probe_scratch_bytes.restype = _i64
         L.hidet_probe_launch_floor.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_float)]
+        L.hidet_probe_stream_bandwidth.argtypes = [_vp, _i64, _i32, _vp, ctypes.POINTER(ctypes.c_float)]
         L.hidet_status_string.argtypes = [_i32]
         L.hidet_status_string.restype = ctypes.c_char_p
         L.hidet_version.restype = ctypes.c_char_p
@@ -514,6 +515,15 @@ def hidet_probe_mfma_peak(sample, mfma=16, stream=None):
                                      _stream(stream), ctypes.byref(tf), ctypes.byref(mhz))
     _check(st, "hidet_probe_mfma_peak")
     return tf.value, mhz.value
+
+
+def hidet_probe_stream_bandwidth(buffer, mode, stream=None):
+    """GB/s of a plain read (mode 0), write (1) or copy (2) kernel walking over `buffer` (a GPU tensor, ideally 1 GiB)."""
+    out = ctypes.c_float(0.0)
+    flat = buffer.reshape(-1)
+    _check(lib().hidet_probe_stream_bandwidth(_ptr(flat), flat.numel() * flat.element_size(), mode, _stream(stream),
+                                              ctypes.byref(out)), "hidet_probe_stream_bandwidth")
+    return out.value
 
 
 def hidet_version():

@@ -128,3 +128,66 @@ extern "C" hidet_status_t hidet_probe_launch_floor(void* stream, int32_t iters, 
   *us_per_launch = ms * 1000.0f / (float)iters;
   return HIDET_OK;
 }
+
+// Streaming rates of plain kernels (measurement aid): what this part sustains when a kernel does nothing but read,
+// write or copy memory that no cache holds -- the ceiling to hold the memory-bound products against, which the
+// datasheet's 8 TB/s is not.  The buffer is walked in pieces of 128 MiB, launch after launch, so that with a buffer of
+// 1 GiB every launch finds its piece in HBM only (the Infinity Cache holds 256 MB).
+namespace {
+typedef unsigned int stream_u32x4 __attribute__((ext_vector_type(4)));
+constexpr long long kPiece = 128LL << 20;
+
+__global__ void __launch_bounds__(256) stream_read_kernel(const stream_u32x4* src, long long n, unsigned* sink) {
+  stream_u32x4 acc = {0u, 0u, 0u, 0u};
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+    acc ^= __builtin_nontemporal_load(src + i);
+  // (never true for the probe's fill pattern; keeps the loads alive)
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) sink[0] = 1u;
+}
+__global__ void __launch_bounds__(256) stream_write_kernel(stream_u32x4* dst, long long n) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+    __builtin_nontemporal_store(stream_u32x4{1u, 2u, 3u, (unsigned)i}, dst + i);
+}
+__global__ void __launch_bounds__(256) stream_copy_kernel(const stream_u32x4* src, stream_u32x4* dst, long long n) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+}  // namespace
+
+extern "C" hidet_status_t hidet_probe_stream_bandwidth(void* buffer, int64_t bytes, int32_t mode, void* stream,
+                                                       float* gbytes_per_s) {
+  if (!buffer || !gbytes_per_s || mode < 0 || mode > 2) return HIDET_ERR_INVALID_ARG;
+  const long long pieces = bytes / kPiece;
+  if (pieces < 2) return HIDET_ERR_INVALID_ARG;  // a copy needs a source and a destination piece
+  if (reinterpret_cast<uintptr_t>(buffer) % 16 != 0) return HIDET_ERR_ALIGNMENT;
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return HIDET_ERR_LAUNCH;
+  unsigned char* base = static_cast<unsigned char*>(buffer);
+  const long long n = kPiece / 16;
+  const int grid = 8192, warm = 8, timed = 40;
+  // (the read kernel's sink is the first word of another piece)
+  auto launch = [&](int it) {
+    unsigned char* a = base + (it % pieces) * kPiece;
+    unsigned char* b = base + ((it + pieces / 2) % pieces) * kPiece;
+    if (mode == 0)
+      hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, s, (const stream_u32x4*)a, n, (unsigned*)b);
+    else if (mode == 1)
+      hipLaunchKernelGGL(stream_write_kernel, dim3(grid), dim3(256), 0, s, (stream_u32x4*)a, n);
+    else
+      hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(256), 0, s, (const stream_u32x4*)a, (stream_u32x4*)b, n);
+  };
+  for (int i = 0; i < warm; ++i) launch(i);
+  (void)hipEventRecord(e0, s);
+  for (int i = 0; i < timed; ++i) launch(warm + i);
+  (void)hipEventRecord(e1, s);
+  float ms = 0.0f;
+  const bool ok = hipGetLastError() == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+                  hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok || ms <= 0.0f) return HIDET_ERR_LAUNCH;
+  const double moved = (mode == 2 ? 2.0 : 1.0) * (double)kPiece * timed;
+  *gbytes_per_s = (float)(moved / (ms * 1e-3) * 1e-9);
+  return HIDET_OK;
+}

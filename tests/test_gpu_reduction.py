@@ -166,3 +166,15 @@ def test_hip_graph_replays_of_the_attention_chain_match_eager():
         V2 = V * 1.0  # unrelated eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(V2, V)
+
+
+def test_stream_bandwidth_probe_reports_plausible_rates():
+    ring = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    rates = [hb.hidet_probe_stream_bandwidth(ring, mode) for mode in range(3)]
+    print("read %.0f write %.0f copy %.0f GB/s" % tuple(rates), flush=True)
+    for r in rates:
+        assert 1000.0 < r < 8000.0  # below the datasheet's HBM rate, far above anything a broken probe reports
+    with pytest.raises(hb.HidetError):
+        hb.hidet_probe_stream_bandwidth(ring, 3)
+    with pytest.raises(hb.HidetError):
+        hb.hidet_probe_stream_bandwidth(ring[: 100 << 20], 0)

@@ -278,6 +278,12 @@ def test_probe_argument_validation():
     assert L.hidet_probe_mfma_peak(hb.HIDET_F16, 16, 0x1000, 8192, 0x2004, n, None, ctypes.byref(f), ctypes.byref(f)) == 3
     assert L.hidet_probe_mfma_peak(9, 16, 0x1000, 8192, 0x2000, n, None, ctypes.byref(f), ctypes.byref(f)) == 1
     assert L.hidet_probe_launch_floor(None, 0, ctypes.byref(f)) == 1 and L.hidet_probe_launch_floor(None, 10, None) == 1
+    gib = 1 << 30
+    assert L.hidet_probe_stream_bandwidth(None, gib, 0, None, ctypes.byref(f)) == 1
+    assert L.hidet_probe_stream_bandwidth(0x1000, gib, 0, None, None) == 1
+    assert L.hidet_probe_stream_bandwidth(0x1000, gib, 3, None, ctypes.byref(f)) == 1
+    assert L.hidet_probe_stream_bandwidth(0x1000, (256 << 20) - 1, 0, None, ctypes.byref(f)) == 1  # fewer than two pieces
+    assert L.hidet_probe_stream_bandwidth(0x1008, gib, 0, None, ctypes.byref(f)) == 3
 
 
 def test_missing_library_fails_loudly(monkeypatch):
