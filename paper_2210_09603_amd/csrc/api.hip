@@ -464,11 +464,12 @@ hipError_t reduce_dispatch(int dtype, const GemmParams& p, int batch, hipStream_
 thread_local long long g_kernel_launches = 0;  // GEMM / convolution kernels this thread has launched so far
 
 // The part of a GEMM (rows or columns, a multiple of 256) that the 256x256 ring tile should take when the rest is
-// better served by a smaller tile; none if both extents are 0.  With T tiles of 256x256, T / 256 whole rounds keep every compute unit busy; a thin last round leaves most
-// of the device idle for 0.6 of a tile's time (measured: it runs at a higher clock than a full round).  At most 64
-// left-over tiles make at most 256 tiles of 128x128, one round that takes 0.3 to 0.45 of that time; more of them
-// would need the 128x256 tile (0.6: no gain) or a second round.  Measured, 4352^3: 196 -> 154 us; 7168^3: 643 -> 602 us.
-// (The cut is made along M or along N, whichever leaves fewer tiles over.)
+// better served by a smaller tile; none if both extents are 0.  With T tiles of 256x256, T / 256 whole rounds keep
+// every compute unit busy; a thin last round leaves most of the device idle for 0.6 of a tile's time (measured: it
+// runs at a higher clock than a full round).  At most 64 left-over tiles make at most 256 tiles of 128x128, one
+// round that takes 0.3 to 0.45 of that time; more of them would need the 128x256 tile (0.6: no gain) or a second
+// round.  Measured, 4352^3: 196 -> 154 us; 7168^3: 643 -> 602 us.  The cut is made along M or along N, whichever
+// leaves fewer tiles over.
 struct RoundCut {
   long long rows = 0, cols = 0;  // at most one is non-zero: extent of the head along M or along N
 };
@@ -485,7 +486,8 @@ RoundCut cut_for_whole_rounds(const Problem& pr, int config, int slices) {
   const long long head_rows = whole * 256 / tn, head_cols = whole * 256 / tm;
   const long long rest_rows = head_rows >= 1 && head_rows < tm ? (tm - head_rows) * tn : -1;
   const long long rest_cols = head_cols >= 1 && head_cols < tn ? (tn - head_cols) * tm : -1;
-  const bool rows_ok = rest_rows >= 0 && rest_rows <= 64, cols_ok = rest_cols >= 0 && rest_cols <= 64;  // one round of 128x128 tiles
+  // (at most 64: one round of 128x128 tiles)
+  const bool rows_ok = rest_rows >= 0 && rest_rows <= 64, cols_ok = rest_cols >= 0 && rest_cols <= 64;
   if (rows_ok && (!cols_ok || rest_rows <= rest_cols))
     cut.rows = head_rows * 256;
   else if (cols_ok)
@@ -511,11 +513,11 @@ hidet_status_t launch(const Problem& pr_in, int config, const SplitK& sk, hipStr
     // (a remembered configuration that has no K-parallel form cannot serve an explicit slice count)
     if (config < 0 || !find_launcher(pr, config) || (slices > 1 && !find_partial_launcher(pr, config)))
       config = default_config(pr, slices);
-    // A GEMM for which the caller named no configuration (size-based or remembered choice), on the 256x256 ring tile,
-    // whose tiles fill whole rounds of the 256 compute units plus a thin last round (at most a quarter full): the
-    // tile rows (or columns) that make up the whole rounds run as they are, the remaining ones run as a problem of their
-    // own, for which the size-based choice takes a smaller tile that fills the device.  Two launches on the same stream, no
-    // partial sums: every output element is still computed by one workgroup over the whole of K.
+    // A GEMM for which the caller named no configuration (size-based or remembered choice), on the 256x256 ring
+    // tile, whose tiles fill whole rounds of the 256 compute units plus a thin last round (at most a quarter full):
+    // the tile rows (or columns) that make up the whole rounds run as they are, the remaining ones run as a problem
+    // of their own, for which the size-based choice takes a smaller tile that fills the device.  Two launches on
+    // the same stream, no partial sums: every output element is still computed by one workgroup over all of K.
     const RoundCut cut = config >= 0 ? cut_for_whole_rounds(pr, config, slices) : RoundCut();
     if (cut.rows > 0 || cut.cols > 0) {
       Problem head = pr, tail = pr;
